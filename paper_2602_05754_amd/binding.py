@@ -1,0 +1,305 @@
+"""ctypes binding of libtf.so.  Argument marshalling only: tensors -> device
+pointers, Python lists -> host arrays.  Names and argument order follow
+include/tf.h.  torch is used for device memory and streams, nothing else."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+TF_F32 = 0
+TF_BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtf.so")
+_lib = None
+
+EXPORTED_SYMBOLS = [
+    "tf_create", "tf_destroy", "tf_strerror", "tf_last_hip_error", "tf_version",
+    "tf_stage_backward", "tf_masked_adamw", "tf_stability_update",
+    "tf_stability_scores", "tf_select_lowest", "tf_num_frozen",
+]
+
+
+class TfError(RuntimeError):
+    def __init__(self, code: int, where: str, hip_error: int = 0):
+        self.code = code
+        self.hip_error = hip_error
+        msg = f"{where}: {tf_strerror(code)} (status {code})"
+        if hip_error:
+            msg += f", hipError_t {hip_error}"
+        super().__init__(msg)
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libtf.so, building it first if it has never been built.  Raises if
+    it cannot be had: there is no fallback implementation."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build
+        build()
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, pp = ctypes.c_void_p, ctypes.POINTER(ctypes.c_void_p)
+    i32, i64, f32, f64 = ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_double
+    lib.tf_create.restype = ctypes.c_int
+    lib.tf_create.argtypes = [pp, ctypes.c_int]
+    lib.tf_destroy.restype = ctypes.c_int
+    lib.tf_destroy.argtypes = [vp]
+    lib.tf_strerror.restype = ctypes.c_char_p
+    lib.tf_strerror.argtypes = [ctypes.c_int]
+    lib.tf_last_hip_error.restype = ctypes.c_int
+    lib.tf_last_hip_error.argtypes = [vp]
+    lib.tf_version.restype = ctypes.c_char_p
+    lib.tf_version.argtypes = []
+    lib.tf_stage_backward.restype = ctypes.c_int
+    lib.tf_stage_backward.argtypes = [vp, vp, i32, vp, i64, ctypes.c_int, vp, vp, vp, vp, vp, vp,
+                                      ctypes.c_int, ctypes.c_int]
+    lib.tf_masked_adamw.restype = ctypes.c_int
+    lib.tf_masked_adamw.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, ctypes.c_int, f32, vp, vp, vp, vp,
+                                    f32, f32, f32, f32, f32, vp, vp, f32, vp]
+    lib.tf_stability_update.restype = ctypes.c_int
+    lib.tf_stability_update.argtypes = [vp, vp, i32, vp, vp, vp, vp, f32, vp, vp, vp]
+    lib.tf_stability_scores.restype = ctypes.c_int
+    lib.tf_stability_scores.argtypes = [vp, i32, vp]
+    lib.tf_select_lowest.restype = ctypes.c_int
+    lib.tf_select_lowest.argtypes = [vp, i32, i32, vp]
+    lib.tf_num_frozen.restype = i32
+    lib.tf_num_frozen.argtypes = [f64, i32]
+    _lib = lib
+    return lib
+
+
+def tf_strerror(code: int) -> str:
+    return load_library().tf_strerror(int(code)).decode()
+
+
+def tf_version() -> str:
+    return load_library().tf_version().decode()
+
+
+# ----------------------------------------------------------------------------
+# marshalling helpers
+# ----------------------------------------------------------------------------
+def _dptr(x) -> Optional[int]:
+    """Device pointer of a torch tensor, or a raw int, or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _ptr_array(seq, n):
+    """Host array of n device pointers (NULL for None); None stays None."""
+    if seq is None:
+        return None, None
+    if len(seq) != n:
+        raise ValueError(f"expected {n} entries, got {len(seq)}")
+    arr = (ctypes.c_void_p * max(n, 1))()
+    for i, x in enumerate(seq):
+        arr[i] = _dptr(x)
+    return arr, ctypes.cast(arr, ctypes.c_void_p)
+
+
+def _host(arr, dtype, n):
+    if arr is None:
+        return None, None
+    a = np.ascontiguousarray(np.asarray(arr, dtype=dtype))
+    if a.size != n:
+        raise ValueError(f"expected {n} entries, got {a.size}")
+    return a, ctypes.c_void_p(a.ctypes.data)
+
+
+def _stream_handle(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream) or None
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+_ELEM_SIZE = {TF_F32: 4, TF_BF16: 2}
+
+
+def _check_numel(x, numel, dtype_code, what):
+    """Host-side guard: a tensor handed to a kernel must hold what the kernel will index."""
+    if x is None or isinstance(x, int):
+        return
+    if x.numel() * x.element_size() < numel * _ELEM_SIZE[dtype_code]:
+        raise ValueError(f"{what}: buffer of {x.numel() * x.element_size()} bytes is smaller than "
+                         f"{numel} elements of {_ELEM_SIZE[dtype_code]} bytes")
+    if not x.is_contiguous():
+        raise ValueError(f"{what}: tensor must be contiguous")
+
+
+class Context:
+    """Owns a tf_ctx bound to one HIP device."""
+
+    def __init__(self, device_id: int = 0):
+        lib = load_library()
+        h = ctypes.c_void_p()
+        rc = lib.tf_create(ctypes.byref(h), int(device_id))
+        if rc != 0:
+            raise TfError(rc, "tf_create")
+        self._h = h
+        self.device_id = device_id
+
+    @property
+    def handle(self):
+        return self._h
+
+    def last_hip_error(self) -> int:
+        return int(load_library().tf_last_hip_error(self._h))
+
+    def close(self):
+        if self._h is not None and self._h.value:
+            load_library().tf_destroy(self._h)
+        self._h = None
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *a):
+        self.close()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def _raise(ctx, rc, where):
+    if rc != 0:
+        hip = 0
+        if ctx is not None and rc == -6:
+            hip = ctx.last_hip_error()
+        raise TfError(rc, where, hip)
+
+
+def _ctx_handle(ctx):
+    return None if ctx is None else ctx.handle
+
+
+# ----------------------------------------------------------------------------
+# entry points (same names as the C ABI)
+# ----------------------------------------------------------------------------
+def tf_stage_backward(ctx, shapes: Sequence[tuple], T: int, io_dtype: int,
+                      W, X, dY, freeze_mask, dX, dW, dw_dtype: int,
+                      accumulate: bool = False, stream=None) -> None:
+    """dX_l = dY_l W_l^T for every layer; dW_l (+)= X_l^T dY_l for layers whose
+    freeze_mask entry is 0.  See include/tf.h."""
+    lib = load_library()
+    L = len(shapes)
+    sh = np.ascontiguousarray(np.asarray(shapes, dtype=np.int64).reshape(L, 2))
+    fm, fm_p = _host(freeze_mask, np.uint8, L)
+    for l in range(L):
+        K, N = int(sh[l, 0]), int(sh[l, 1])
+        frozen = fm is not None and fm[l]
+        if W is not None: _check_numel(W[l], K * N, io_dtype, f"W[{l}]")
+        if dY is not None: _check_numel(dY[l], T * N, io_dtype, f"dY[{l}]")
+        if dX is not None: _check_numel(dX[l], T * K, io_dtype, f"dX[{l}]")
+        if not frozen:
+            if X is not None: _check_numel(X[l], T * K, io_dtype, f"X[{l}]")
+            if dW is not None: _check_numel(dW[l], K * N, dw_dtype, f"dW[{l}]")
+    kW, pW = _ptr_array(W, L)
+    kX, pX = _ptr_array(X, L)
+    kdY, pdY = _ptr_array(dY, L)
+    kdX, pdX = _ptr_array(dX, L)
+    kdW, pdW = _ptr_array(dW, L)
+    rc = lib.tf_stage_backward(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
+                               L, sh.ctypes.data, int(T), int(io_dtype),
+                               pW, pX, pdY, fm_p, pdX, pdW, int(dw_dtype), 1 if accumulate else 0)
+    _raise(ctx, rc, "tf_stage_backward")
+
+
+def tf_masked_adamw(ctx, numel: Sequence[int], p_master, m, v, grad, grad_dtype: int,
+                    step: Sequence[int], lr: float, beta1: float, beta2: float, eps: float,
+                    weight_decay: float, grad_scale: float = 1.0, p_lowp=None,
+                    tensor_freeze_mask=None, elem_freeze_bits=None,
+                    ema=None, ema_abs=None, ema_decay: float = 0.0, score_sums=None,
+                    stream=None) -> None:
+    """Masked AdamW step, optionally fused with the APF EMAs.  See include/tf.h."""
+    lib = load_library()
+    n = len(numel)
+    ne, ne_p = _host(numel, np.int64, n)
+    st, st_p = _host(step, np.int32, n)
+    fm, fm_p = _host(tensor_freeze_mask, np.uint8, n)
+    for i in range(n):
+        if fm is not None and fm[i]:
+            continue
+        for name, seq, dt in (("p", p_master, TF_F32), ("m", m, TF_F32), ("v", v, TF_F32),
+                              ("grad", grad, grad_dtype), ("p_lowp", p_lowp, TF_BF16),
+                              ("ema", ema, TF_F32), ("ema_abs", ema_abs, TF_F32)):
+            if seq is not None:
+                _check_numel(seq[i], int(ne[i]), dt, f"{name}[{i}]")
+        if elem_freeze_bits is not None and elem_freeze_bits[i] is not None and not isinstance(elem_freeze_bits[i], int):
+            if elem_freeze_bits[i].numel() * elem_freeze_bits[i].element_size() < 4 * ((int(ne[i]) + 31) // 32):
+                raise ValueError(f"elem_freeze_bits[{i}] too small")
+    if score_sums is not None and not isinstance(score_sums, int):
+        if score_sums.numel() * score_sums.element_size() < 16 * n:
+            raise ValueError("score_sums too small")
+    keep = [_ptr_array(s, n) for s in (p_master, m, v, grad, p_lowp, elem_freeze_bits, ema, ema_abs)]
+    pp = [k[1] for k in keep]
+    rc = lib.tf_masked_adamw(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
+                             n, ne_p, pp[0], pp[1], pp[2], pp[3], int(grad_dtype), float(grad_scale),
+                             pp[4], fm_p, pp[5], st_p,
+                             float(lr), float(beta1), float(beta2), float(eps), float(weight_decay),
+                             pp[6], pp[7], float(ema_decay), _dptr(score_sums))
+    _raise(ctx, rc, "tf_masked_adamw")
+
+
+def tf_stability_update(ctx, numel: Sequence[int], delta, ema, ema_abs, ema_decay: float,
+                        tensor_freeze_mask=None, elem_freeze_bits=None, score_sums=None,
+                        stream=None) -> None:
+    """Stand-alone APF EMA update from an explicit fp32 delta.  See include/tf.h."""
+    lib = load_library()
+    n = len(numel)
+    ne, ne_p = _host(numel, np.int64, n)
+    fm, fm_p = _host(tensor_freeze_mask, np.uint8, n)
+    for i in range(n):
+        if fm is not None and fm[i]:
+            continue
+        for name, seq in (("delta", delta), ("ema", ema), ("ema_abs", ema_abs)):
+            if seq is not None:
+                _check_numel(seq[i], int(ne[i]), TF_F32, f"{name}[{i}]")
+    keep = [_ptr_array(s, n) for s in (delta, ema, ema_abs, elem_freeze_bits)]
+    pp = [k[1] for k in keep]
+    rc = lib.tf_stability_update(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
+                                 n, ne_p, pp[0], pp[1], pp[2], float(ema_decay), fm_p, pp[3],
+                                 _dptr(score_sums))
+    _raise(ctx, rc, "tf_stability_update")
+
+
+def tf_stability_scores(score_sums_host) -> np.ndarray:
+    """Host: per-tensor score = sum|E| / sum A from a host copy of score_sums."""
+    lib = load_library()
+    s = np.ascontiguousarray(np.asarray(score_sums_host, dtype=np.float64).reshape(-1))
+    n = s.size // 2
+    out = np.empty(n, dtype=np.float64)
+    rc = lib.tf_stability_scores(s.ctypes.data, n, out.ctypes.data)
+    _raise(None, rc, "tf_stability_scores")
+    return out
+
+
+def tf_select_lowest(scores, n_freeze: int) -> np.ndarray:
+    """Host: uint8 mask, 1 for the n_freeze lowest scores (ties -> lower index)."""
+    lib = load_library()
+    s = np.ascontiguousarray(np.asarray(scores, dtype=np.float64).reshape(-1))
+    out = np.zeros(max(s.size, 1), dtype=np.uint8)
+    rc = lib.tf_select_lowest(s.ctypes.data, s.size, int(n_freeze), out.ctypes.data)
+    _raise(None, rc, "tf_select_lowest")
+    return out[: s.size]
+
+
+def tf_num_frozen(r: float, n: int) -> int:
+    return int(load_library().tf_num_frozen(float(r), int(n)))

@@ -1,0 +1,266 @@
+// Fused masked AdamW + APF stability pass, and the stand-alone stability update.
+//
+// TimelyFreeze App. D.1: mask value 1 = frozen = no update (U = 1 - I); the
+// optimizer is AdamW (Table exp_setup).  Sec. 2.3 (APF): E <- aE + (1-a)Delta,
+// E^abs <- aE^abs + (1-a)|Delta|, with Delta = the update just applied.
+//
+// HBM-bound: per unfrozen element 22 B are read (p, m, v, E, A fp32 + bf16
+// grad) and 22 B written (p, m, v, E, A + bf16 copy of p).  Each thread owns
+// groups of 8 consecutive elements so that every access is a 16-byte vector
+// (two for fp32 arrays); a frozen element is written back with the very bits
+// that were read, a fully frozen group is neither read nor written.
+#include "tf_internal.h"
+
+namespace tf {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kGroup = 8;          // elements per thread per iteration
+constexpr int kIters = 2;          // iterations per block
+constexpr int64_t kElemsPerBlock = int64_t(kThreads) * kGroup * kIters;
+
+struct alignas(16) F4 { float x, y, z, w; };
+struct alignas(16) U4 { uint32_t x, y, z, w; };
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+// binary32 -> bf16 bits, round to nearest even (NaN stays NaN).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ void load8(const float* ptr, float (&out)[8]) {
+    const F4 a = *reinterpret_cast<const F4*>(ptr);
+    const F4 b = *reinterpret_cast<const F4*>(ptr + 4);
+    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+    out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+}
+
+__device__ __forceinline__ void store8(float* ptr, const float (&in)[8]) {
+    *reinterpret_cast<F4*>(ptr) = F4{in[0], in[1], in[2], in[3]};
+    *reinterpret_cast<F4*>(ptr + 4) = F4{in[4], in[5], in[6], in[7]};
+}
+
+// One element of the AdamW step; returns the applied update u = p_new - p_old.
+__device__ __forceinline__ float adamw_elem(float& p, float& m, float& v, float g,
+                                            const AdamwParams& hp, float rbc1, float rbc2) {
+    m = hp.beta1 * m + hp.one_minus_beta1 * g;
+    v = hp.beta2 * v + hp.one_minus_beta2 * (g * g);
+    const float mhat = m * rbc1;
+    const float vhat = v * rbc2;
+    const float u = -(hp.lr * hp.weight_decay) * p - hp.lr * (mhat / (sqrtf(vhat) + hp.eps));
+    p = p + u;
+    return u;
+}
+
+__device__ __forceinline__ void ema_elem(float& E, float& A, float delta, const AdamwParams& hp) {
+    E = hp.ema_decay * E + hp.one_minus_ema_decay * delta;
+    A = hp.ema_decay * A + hp.one_minus_ema_decay * fabsf(delta);
+}
+
+__global__ void zero_sums_kernel(EwBatch batch) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < batch.n_tensors && batch.t[i].sums) {
+        batch.t[i].sums[0] = 0.0;
+        batch.t[i].sums[1] = 0.0;
+    }
+}
+
+// kAdamw: full AdamW (+ EMAs if E != nullptr).  !kAdamw: EMAs from an explicit fp32 delta.
+template <bool kAdamw, bool kGradBf16>
+__global__ __launch_bounds__(kThreads) void ew_kernel(EwBatch batch, AdamwParams hp) {
+    // locate this block's tensor (block-uniform scan over <= 32 entries)
+    int ti = 0;
+    const int bid = blockIdx.x;
+    for (int i = 1; i < batch.n_tensors; ++i)
+        if (bid >= batch.t[i].block_start) ti = i;
+    const EwTensor& T = batch.t[ti];
+    const int64_t numel = T.numel;
+    const int64_t chunk = int64_t(bid - T.block_start) * kElemsPerBlock;
+    const bool has_ema = T.E != nullptr;
+    const bool want_sums = T.sums != nullptr;
+    const uint8_t* mask_bytes = reinterpret_cast<const uint8_t*>(T.bits);
+
+    double sum_e = 0.0, sum_a = 0.0;
+
+#pragma unroll
+    for (int it = 0; it < kIters; ++it) {
+        const int64_t e0 = chunk + (int64_t(it) * kThreads + threadIdx.x) * kGroup;
+        if (e0 >= numel) continue;
+        if (e0 + kGroup <= numel) {
+            // ---------------- vector path: 8 elements ----------------
+            const uint32_t fz = mask_bytes ? uint32_t(mask_bytes[e0 >> 3]) : 0u;
+            if (fz == 0xffu) {
+                if (want_sums) {
+                    float E[8], A[8];
+                    load8(T.E + e0, E);
+                    load8(T.A + e0, A);
+                    float se = 0.f, sa = 0.f;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) { se += fabsf(E[j]); sa += A[j]; }
+                    sum_e += double(se); sum_a += double(sa);
+                }
+                continue;
+            }
+            float p[8], m[8], v[8], g[8], E[8], A[8];
+            if (kAdamw) {
+                load8(T.p + e0, p);
+                load8(T.m + e0, m);
+                load8(T.v + e0, v);
+                if (kGradBf16) {
+                    const U4 q = *reinterpret_cast<const U4*>(static_cast<const uint16_t*>(T.g) + e0);
+                    g[0] = bf16_bits_to_f32(q.x & 0xffffu); g[1] = bf16_bits_to_f32(q.x >> 16);
+                    g[2] = bf16_bits_to_f32(q.y & 0xffffu); g[3] = bf16_bits_to_f32(q.y >> 16);
+                    g[4] = bf16_bits_to_f32(q.z & 0xffffu); g[5] = bf16_bits_to_f32(q.z >> 16);
+                    g[6] = bf16_bits_to_f32(q.w & 0xffffu); g[7] = bf16_bits_to_f32(q.w >> 16);
+                } else {
+                    load8(static_cast<const float*>(T.g) + e0, g);
+                }
+            } else {
+                load8(static_cast<const float*>(T.g) + e0, g);
+            }
+            if (has_ema) {
+                load8(T.E + e0, E);
+                load8(T.A + e0, A);
+            }
+            U4 low_old = U4{0, 0, 0, 0};
+            const bool has_low = kAdamw && T.p_lowp != nullptr;
+            if (has_low && fz != 0u) low_old = *reinterpret_cast<const U4*>(T.p_lowp + e0);
+
+            uint32_t low[8];
+            float se = 0.f, sa = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const bool frozen = (fz >> j) & 1u;
+                float pn = 0.f, mn = 0.f, vn = 0.f, En = 0.f, An = 0.f;
+                if (kAdamw) {
+                    pn = p[j]; mn = m[j]; vn = v[j];
+                    const float u = adamw_elem(pn, mn, vn, hp.grad_scale * g[j], hp, T.rbc1, T.rbc2);
+                    if (has_ema) { En = E[j]; An = A[j]; ema_elem(En, An, u, hp); }
+                    low[j] = f32_to_bf16_bits(pn);
+                    p[j] = frozen ? p[j] : pn;
+                    m[j] = frozen ? m[j] : mn;
+                    v[j] = frozen ? v[j] : vn;
+                } else {
+                    En = E[j]; An = A[j]; ema_elem(En, An, g[j], hp);
+                }
+                if (has_ema) {
+                    E[j] = frozen ? E[j] : En;
+                    A[j] = frozen ? A[j] : An;
+                    se += fabsf(E[j]); sa += A[j];
+                }
+            }
+            if (kAdamw) {
+                store8(T.p + e0, p);
+                store8(T.m + e0, m);
+                store8(T.v + e0, v);
+                if (has_low) {
+                    U4 o;
+                    o.x = low[0] | (low[1] << 16); o.y = low[2] | (low[3] << 16);
+                    o.z = low[4] | (low[5] << 16); o.w = low[6] | (low[7] << 16);
+                    if (fz != 0u) {
+                        // keep the stored bf16 of frozen elements
+                        const uint32_t k0 = ((fz & 1u) ? 0xffffu : 0u) | ((fz & 2u) ? 0xffff0000u : 0u);
+                        const uint32_t k1 = ((fz & 4u) ? 0xffffu : 0u) | ((fz & 8u) ? 0xffff0000u : 0u);
+                        const uint32_t k2 = ((fz & 16u) ? 0xffffu : 0u) | ((fz & 32u) ? 0xffff0000u : 0u);
+                        const uint32_t k3 = ((fz & 64u) ? 0xffffu : 0u) | ((fz & 128u) ? 0xffff0000u : 0u);
+                        o.x = (o.x & ~k0) | (low_old.x & k0);
+                        o.y = (o.y & ~k1) | (low_old.y & k1);
+                        o.z = (o.z & ~k2) | (low_old.z & k2);
+                        o.w = (o.w & ~k3) | (low_old.w & k3);
+                    }
+                    *reinterpret_cast<U4*>(T.p_lowp + e0) = o;
+                }
+            }
+            if (has_ema) {
+                store8(T.E + e0, E);
+                store8(T.A + e0, A);
+                sum_e += double(se); sum_a += double(sa);
+            }
+        } else {
+            // ---------------- ragged tail: < 8 elements, one at a time ----------------
+            for (int64_t e = e0; e < numel; ++e) {
+                const bool frozen = T.bits && ((T.bits[e >> 5] >> (e & 31)) & 1u);
+                if (frozen) {
+                    if (want_sums) { sum_e += double(fabsf(T.E[e])); sum_a += double(T.A[e]); }
+                    continue;
+                }
+                float u;
+                if (kAdamw) {
+                    float pn = T.p[e], mn = T.m[e], vn = T.v[e];
+                    float gj;
+                    if (kGradBf16) gj = bf16_bits_to_f32(static_cast<const uint16_t*>(T.g)[e]);
+                    else gj = static_cast<const float*>(T.g)[e];
+                    u = adamw_elem(pn, mn, vn, hp.grad_scale * gj, hp, T.rbc1, T.rbc2);
+                    T.p[e] = pn; T.m[e] = mn; T.v[e] = vn;
+                    if (T.p_lowp) T.p_lowp[e] = uint16_t(f32_to_bf16_bits(pn));
+                } else {
+                    u = static_cast<const float*>(T.g)[e];
+                }
+                if (has_ema) {
+                    float En = T.E[e], An = T.A[e];
+                    ema_elem(En, An, u, hp);
+                    T.E[e] = En; T.A[e] = An;
+                    sum_e += double(fabsf(En)); sum_a += double(An);
+                }
+            }
+        }
+    }
+
+    if (want_sums) {
+        // wave reduction (64 lanes), then across the 4 waves through LDS, then one fp64 atomic pair
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            sum_e += __shfl_down(sum_e, off, 64);
+            sum_a += __shfl_down(sum_a, off, 64);
+        }
+        __shared__ double red[2][kThreads / 64];
+        const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+        if (lane == 0) { red[0][wave] = sum_e; red[1][wave] = sum_a; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double a = 0.0, b = 0.0;
+#pragma unroll
+            for (int w = 0; w < kThreads / 64; ++w) { a += red[0][w]; b += red[1][w]; }
+            unsafeAtomicAdd(T.sums + 0, a);
+            unsafeAtomicAdd(T.sums + 1, b);
+        }
+    }
+}
+
+bool any_sums(const EwBatch& b, int n) {
+    for (int i = 0; i < n; ++i)
+        if (b.t[i].sums) return true;
+    return false;
+}
+
+}  // namespace
+
+int64_t ew_elems_per_block() { return kElemsPerBlock; }
+
+hipError_t launch_adamw(hipStream_t stream, EwBatch& batch, int n_tensors,
+                        const AdamwParams& hp, Dtype grad_dtype) {
+    batch.n_tensors = n_tensors;
+    if (n_tensors == 0 || batch.total_blocks == 0) return hipSuccess;
+    if (any_sums(batch, n_tensors))
+        hipLaunchKernelGGL(zero_sums_kernel, dim3(1), dim3(64), 0, stream, batch);
+    if (grad_dtype == Dtype::BF16)
+        hipLaunchKernelGGL((ew_kernel<true, true>), dim3(batch.total_blocks), dim3(kThreads), 0, stream, batch, hp);
+    else
+        hipLaunchKernelGGL((ew_kernel<true, false>), dim3(batch.total_blocks), dim3(kThreads), 0, stream, batch, hp);
+    return hipGetLastError();
+}
+
+hipError_t launch_stability(hipStream_t stream, EwBatch& batch, int n_tensors,
+                            const AdamwParams& hp) {
+    batch.n_tensors = n_tensors;
+    if (n_tensors == 0 || batch.total_blocks == 0) return hipSuccess;
+    if (any_sums(batch, n_tensors))
+        hipLaunchKernelGGL(zero_sums_kernel, dim3(1), dim3(64), 0, stream, batch);
+    hipLaunchKernelGGL((ew_kernel<false, false>), dim3(batch.total_blocks), dim3(kThreads), 0, stream, batch, hp);
+    return hipGetLastError();
+}
+
+}  // namespace tf

@@ -1,0 +1,388 @@
+// C ABI of libtf.so: argument validation, host-side planning (which layers go
+// into which grouped launch; frozen tensors are left out of the weight-gradient
+// plan entirely) and kernel launches.  Declarations and contracts: include/tf.h.
+#include "../../include/tf.h"
+#include "tf_internal.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+struct tf_ctx {
+    int device_id;
+    int last_hip_error;
+};
+
+namespace {
+
+using namespace tf;
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool valid_dtype(int d) { return d == TF_F32 || d == TF_BF16; }
+inline Dtype to_dtype(tf_dtype d) { return d == TF_BF16 ? Dtype::BF16 : Dtype::F32; }
+
+int hip_fail(tf_ctx* ctx, hipError_t e) {
+    ctx->last_hip_error = static_cast<int>(e);
+    return TF_ERR_HIP;
+}
+
+// One planned GEMM: which layer, as which problem.
+struct Planned {
+    const void* A;
+    const void* B;
+    void* C;
+    int64_t M, N, Kc;
+};
+
+// Launch `items` in batches of at most kMaxProblemsPerLaunch, MFMA-eligible ones on the
+// matrix cores, the rest on the generic kernel.
+hipError_t launch_planned(hipStream_t stream, std::vector<Planned>& items, Layout layout,
+                          Dtype in_dtype, Dtype out_dtype, bool accumulate) {
+    std::vector<Planned> fast, slow;
+    for (const Planned& it : items) {
+        if (in_dtype == Dtype::BF16 && mfma_shape_ok(it.M, it.N, it.Kc)) fast.push_back(it);
+        else slow.push_back(it);
+    }
+    // Longest contraction first: the tail of a launch is then made of the cheapest tiles.
+    auto by_cost = [](const Planned& a, const Planned& b) { return a.Kc > b.Kc; };
+    std::stable_sort(fast.begin(), fast.end(), by_cost);
+    std::stable_sort(slow.begin(), slow.end(), by_cost);
+
+    GemmBatch batch;
+    for (int pass = 0; pass < 2; ++pass) {
+        const std::vector<Planned>& v = pass == 0 ? fast : slow;
+        const int64_t tile = pass == 0 ? gemm_mfma_tile() : gemm_generic_tile();
+        size_t i = 0;
+        while (i < v.size()) {
+            int n = 0;
+            int64_t tiles = 0;
+            while (i < v.size() && n < kMaxProblemsPerLaunch) {
+                const Planned& it = v[i];
+                const int64_t nt = ((it.M + tile - 1) / tile) * ((it.N + tile - 1) / tile);
+                if (n > 0 && tiles + nt > 0x3fffffff) break;
+                GemmProblem& gp = batch.p[n];
+                gp.A = it.A; gp.B = it.B; gp.C = it.C;
+                gp.M = int32_t(it.M); gp.N = int32_t(it.N); gp.Kc = int32_t(it.Kc);
+                gp.tile_start = int32_t(tiles);
+                tiles += nt;
+                ++n; ++i;
+            }
+            batch.total_tiles = int32_t(tiles);
+            const hipError_t e = pass == 0
+                ? launch_gemm_mfma_bf16(stream, batch, n, layout, out_dtype, accumulate)
+                : launch_gemm_generic(stream, batch, n, layout, in_dtype, out_dtype, accumulate);
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
+}
+
+int validate_elementwise_common(int32_t n_tensors, const int64_t* numel,
+                                void* const* ema, void* const* ema_abs,
+                                const uint8_t* tensor_freeze_mask,
+                                const uint32_t* const* elem_freeze_bits,
+                                const double* score_sums, float ema_decay, bool ema_required) {
+    if (n_tensors < 0) return TF_ERR_INVALID_ARG;
+    if (n_tensors == 0) return TF_OK;
+    if (!numel) return TF_ERR_INVALID_ARG;
+    if ((ema == nullptr) != (ema_abs == nullptr)) return TF_ERR_INVALID_ARG;
+    if (ema_required && !ema) return TF_ERR_INVALID_ARG;
+    if (score_sums && !ema) return TF_ERR_INVALID_ARG;
+    if (ema && !(ema_decay >= 0.f && ema_decay <= 1.f)) return TF_ERR_INVALID_ARG;
+    if (score_sums && (reinterpret_cast<uintptr_t>(score_sums) & 7u)) return TF_ERR_ALIGN;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (numel[i] <= 0) return TF_ERR_SHAPE;
+        if (numel[i] > (int64_t(1) << 40)) return TF_ERR_SHAPE;
+        if (tensor_freeze_mask && tensor_freeze_mask[i] > 1) return TF_ERR_INVALID_ARG;
+        if (tensor_freeze_mask && tensor_freeze_mask[i]) continue;
+        if (ema) {
+            if (!ema[i] || !ema_abs[i]) return TF_ERR_INVALID_ARG;
+            if (!aligned16(ema[i]) || !aligned16(ema_abs[i])) return TF_ERR_ALIGN;
+        }
+        if (elem_freeze_bits && elem_freeze_bits[i] && !aligned16(elem_freeze_bits[i])) return TF_ERR_ALIGN;
+    }
+    return TF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* tf_version(void) { return "0.1.0"; }
+
+const char* tf_strerror(int code) {
+    switch (code) {
+        case TF_OK: return "ok";
+        case TF_ERR_INVALID_ARG: return "invalid argument";
+        case TF_ERR_SHAPE: return "invalid shape or size";
+        case TF_ERR_DTYPE: return "unsupported dtype or dtype combination";
+        case TF_ERR_ALIGN: return "device pointer is not 16-byte aligned";
+        case TF_ERR_WORKSPACE: return "workspace allocation failed";
+        case TF_ERR_HIP: return "HIP runtime error (see tf_last_hip_error)";
+        case TF_ERR_NO_DEVICE: return "no usable gfx950 device";
+        default: return "unknown status code";
+    }
+}
+
+int tf_create(tf_ctx** out, int device_id) {
+    if (!out || device_id < 0) return TF_ERR_INVALID_ARG;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device_id >= count) return TF_ERR_NO_DEVICE;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) return TF_ERR_NO_DEVICE;
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return TF_ERR_NO_DEVICE;
+    if (hipSetDevice(device_id) != hipSuccess) return TF_ERR_NO_DEVICE;
+    tf_ctx* ctx = new (std::nothrow) tf_ctx;
+    if (!ctx) return TF_ERR_WORKSPACE;
+    ctx->device_id = device_id;
+    ctx->last_hip_error = 0;
+    *out = ctx;
+    return TF_OK;
+}
+
+int tf_destroy(tf_ctx* ctx) {
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    delete ctx;
+    return TF_OK;
+}
+
+int tf_last_hip_error(const tf_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
+
+int tf_stage_backward(tf_ctx* ctx, void* hip_stream,
+                      int32_t n_layers, const tf_shape* shapes,
+                      int64_t T, tf_dtype io_dtype,
+                      const void* const* W, const void* const* X, const void* const* dY,
+                      const uint8_t* freeze_mask,
+                      void* const* dX,
+                      void* const* dW, tf_dtype dw_dtype,
+                      int accumulate) {
+    // ---- validation: no HIP call before this block has passed ----
+    if (n_layers < 0) return TF_ERR_INVALID_ARG;
+    if (!valid_dtype(io_dtype) || !valid_dtype(dw_dtype)) return TF_ERR_DTYPE;
+    if (accumulate != 0 && accumulate != 1) return TF_ERR_INVALID_ARG;
+    if (accumulate && dw_dtype != TF_F32) return TF_ERR_DTYPE;
+    if (io_dtype == TF_F32 && dw_dtype != TF_F32) return TF_ERR_DTYPE;
+    if (n_layers > 0) {
+        if (!shapes || !W || !dY || !dX) return TF_ERR_INVALID_ARG;
+        if (T <= 0 || T > 0x7fffffff) return TF_ERR_SHAPE;
+        bool any_unfrozen = false;
+        for (int32_t l = 0; l < n_layers; ++l) {
+            if (shapes[l].K <= 0 || shapes[l].N <= 0) return TF_ERR_SHAPE;
+            if (shapes[l].K > 0x7fffffff || shapes[l].N > 0x7fffffff) return TF_ERR_SHAPE;
+            if (freeze_mask && freeze_mask[l] > 1) return TF_ERR_INVALID_ARG;
+            if (!W[l] || !dY[l] || !dX[l]) return TF_ERR_INVALID_ARG;
+            if (!aligned16(W[l]) || !aligned16(dY[l]) || !aligned16(dX[l])) return TF_ERR_ALIGN;
+            if (!(freeze_mask && freeze_mask[l])) any_unfrozen = true;
+        }
+        if (any_unfrozen && (!X || !dW)) return TF_ERR_INVALID_ARG;
+        for (int32_t l = 0; l < n_layers; ++l) {
+            if (freeze_mask && freeze_mask[l]) continue;
+            if (!X[l] || !dW[l]) return TF_ERR_INVALID_ARG;
+            if (!aligned16(X[l]) || !aligned16(dW[l])) return TF_ERR_ALIGN;
+        }
+    }
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    if (n_layers == 0) return TF_OK;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const Dtype in_dt = to_dtype(io_dtype);
+
+    // input gradients: every layer, whatever the mask says
+    std::vector<Planned> plan;
+    plan.reserve(n_layers);
+    for (int32_t l = 0; l < n_layers; ++l)
+        plan.push_back(Planned{dY[l], W[l], dX[l], T, shapes[l].K, shapes[l].N});
+    hipError_t e = launch_planned(stream, plan, Layout::kNT, in_dt, in_dt, false);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+
+    // weight gradients: unfrozen layers only; a frozen layer is simply not in the plan
+    plan.clear();
+    for (int32_t l = 0; l < n_layers; ++l) {
+        if (freeze_mask && freeze_mask[l]) continue;
+        plan.push_back(Planned{X[l], dY[l], dW[l], shapes[l].K, shapes[l].N, T});
+    }
+    e = launch_planned(stream, plan, Layout::kTN, in_dt, to_dtype(dw_dtype), accumulate != 0);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return TF_OK;
+}
+
+int tf_masked_adamw(tf_ctx* ctx, void* hip_stream,
+                    int32_t n_tensors, const int64_t* numel,
+                    void* const* p_master, void* const* m, void* const* v,
+                    const void* const* grad, tf_dtype grad_dtype, float grad_scale,
+                    void* const* p_lowp,
+                    const uint8_t* tensor_freeze_mask,
+                    const uint32_t* const* elem_freeze_bits,
+                    const int32_t* step,
+                    float lr, float beta1, float beta2, float eps, float weight_decay,
+                    void* const* ema, void* const* ema_abs, float ema_decay,
+                    double* score_sums) {
+    if (!valid_dtype(grad_dtype)) return TF_ERR_DTYPE;
+    int rc = validate_elementwise_common(n_tensors, numel, ema, ema_abs, tensor_freeze_mask,
+                                         elem_freeze_bits, score_sums, ema_decay, false);
+    if (rc != TF_OK) return rc;
+    if (n_tensors > 0) {
+        if (!p_master || !m || !v || !grad || !step) return TF_ERR_INVALID_ARG;
+        if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f)) return TF_ERR_INVALID_ARG;
+        if (!(eps >= 0.f) || !std::isfinite(lr) || !std::isfinite(weight_decay) || !std::isfinite(grad_scale))
+            return TF_ERR_INVALID_ARG;
+        for (int32_t i = 0; i < n_tensors; ++i) {
+            if (tensor_freeze_mask && tensor_freeze_mask[i]) continue;
+            if (step[i] < 1) return TF_ERR_INVALID_ARG;
+            if (!p_master[i] || !m[i] || !v[i] || !grad[i]) return TF_ERR_INVALID_ARG;
+            if (!aligned16(p_master[i]) || !aligned16(m[i]) || !aligned16(v[i]) || !aligned16(grad[i]))
+                return TF_ERR_ALIGN;
+            if (p_lowp && p_lowp[i] && !aligned16(p_lowp[i])) return TF_ERR_ALIGN;
+        }
+    }
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    if (n_tensors == 0) return TF_OK;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    AdamwParams hp;
+    hp.grad_scale = grad_scale;
+    hp.lr = lr; hp.beta1 = beta1; hp.beta2 = beta2; hp.eps = eps; hp.weight_decay = weight_decay;
+    hp.one_minus_beta1 = float(1.0 - double(beta1));
+    hp.one_minus_beta2 = float(1.0 - double(beta2));
+    hp.ema_decay = ema_decay;
+    hp.one_minus_ema_decay = float(1.0 - double(ema_decay));
+
+    const int64_t epb = ew_elems_per_block();
+    EwBatch batch;
+    int n = 0;
+    int64_t blocks = 0;
+    auto flush = [&]() -> hipError_t {
+        batch.total_blocks = int32_t(blocks);
+        const hipError_t e = launch_adamw(stream, batch, n, hp, to_dtype(grad_dtype));
+        n = 0; blocks = 0;
+        return e;
+    };
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (tensor_freeze_mask && tensor_freeze_mask[i]) continue;   // frozen: not even read
+        const int64_t nb = (numel[i] + epb - 1) / epb;
+        if (n == kMaxTensorsPerLaunch || (n > 0 && blocks + nb > 0x3fffffff)) {
+            const hipError_t e = flush();
+            if (e != hipSuccess) return hip_fail(ctx, e);
+        }
+        EwTensor& t = batch.t[n];
+        t.p = static_cast<float*>(p_master[i]);
+        t.m = static_cast<float*>(m[i]);
+        t.v = static_cast<float*>(v[i]);
+        t.g = grad[i];
+        t.p_lowp = p_lowp ? static_cast<uint16_t*>(p_lowp[i]) : nullptr;
+        t.bits = elem_freeze_bits ? elem_freeze_bits[i] : nullptr;
+        t.E = ema ? static_cast<float*>(ema[i]) : nullptr;
+        t.A = ema ? static_cast<float*>(ema_abs[i]) : nullptr;
+        t.sums = score_sums ? score_sums + 2 * int64_t(i) : nullptr;
+        t.numel = numel[i];
+        t.rbc1 = float(1.0 / (1.0 - std::pow(double(beta1), double(step[i]))));
+        t.rbc2 = float(1.0 / (1.0 - std::pow(double(beta2), double(step[i]))));
+        t.block_start = int32_t(blocks);
+        t.pad_ = 0;
+        blocks += nb;
+        ++n;
+    }
+    if (n > 0) {
+        const hipError_t e = flush();
+        if (e != hipSuccess) return hip_fail(ctx, e);
+    }
+    return TF_OK;
+}
+
+int tf_stability_update(tf_ctx* ctx, void* hip_stream,
+                        int32_t n_tensors, const int64_t* numel,
+                        const void* const* delta,
+                        void* const* ema, void* const* ema_abs, float ema_decay,
+                        const uint8_t* tensor_freeze_mask,
+                        const uint32_t* const* elem_freeze_bits,
+                        double* score_sums) {
+    int rc = validate_elementwise_common(n_tensors, numel, ema, ema_abs, tensor_freeze_mask,
+                                         elem_freeze_bits, score_sums, ema_decay, true);
+    if (rc != TF_OK) return rc;
+    if (n_tensors > 0) {
+        if (!delta) return TF_ERR_INVALID_ARG;
+        for (int32_t i = 0; i < n_tensors; ++i) {
+            if (tensor_freeze_mask && tensor_freeze_mask[i]) continue;
+            if (!delta[i]) return TF_ERR_INVALID_ARG;
+            if (!aligned16(delta[i])) return TF_ERR_ALIGN;
+        }
+    }
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    if (n_tensors == 0) return TF_OK;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    AdamwParams hp;
+    std::memset(&hp, 0, sizeof(hp));
+    hp.ema_decay = ema_decay;
+    hp.one_minus_ema_decay = float(1.0 - double(ema_decay));
+
+    const int64_t epb = ew_elems_per_block();
+    EwBatch batch;
+    int n = 0;
+    int64_t blocks = 0;
+    auto flush = [&]() -> hipError_t {
+        batch.total_blocks = int32_t(blocks);
+        const hipError_t e = launch_stability(stream, batch, n, hp);
+        n = 0; blocks = 0;
+        return e;
+    };
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (tensor_freeze_mask && tensor_freeze_mask[i]) continue;
+        const int64_t nb = (numel[i] + epb - 1) / epb;
+        if (n == kMaxTensorsPerLaunch || (n > 0 && blocks + nb > 0x3fffffff)) {
+            const hipError_t e = flush();
+            if (e != hipSuccess) return hip_fail(ctx, e);
+        }
+        EwTensor& t = batch.t[n];
+        std::memset(&t, 0, sizeof(t));
+        t.g = delta[i];
+        t.bits = elem_freeze_bits ? elem_freeze_bits[i] : nullptr;
+        t.E = static_cast<float*>(ema[i]);
+        t.A = static_cast<float*>(ema_abs[i]);
+        t.sums = score_sums ? score_sums + 2 * int64_t(i) : nullptr;
+        t.numel = numel[i];
+        t.block_start = int32_t(blocks);
+        blocks += nb;
+        ++n;
+    }
+    if (n > 0) {
+        const hipError_t e = flush();
+        if (e != hipSuccess) return hip_fail(ctx, e);
+    }
+    return TF_OK;
+}
+
+int tf_stability_scores(const double* score_sums, int32_t n, double* scores) {
+    if (n < 0 || (n > 0 && (!score_sums || !scores))) return TF_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i) {
+        const double se = score_sums[2 * i], sa = score_sums[2 * i + 1];
+        scores[i] = (sa == 0.0) ? 1.0 : se / sa;
+    }
+    return TF_OK;
+}
+
+int tf_select_lowest(const double* scores, int32_t n, int32_t n_freeze, uint8_t* out_mask) {
+    if (n < 0 || n_freeze < 0 || n_freeze > n) return TF_ERR_INVALID_ARG;
+    if (n > 0 && (!scores || !out_mask)) return TF_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i)
+        if (std::isnan(scores[i])) return TF_ERR_INVALID_ARG;
+    std::vector<int32_t> order(n);
+    for (int32_t i = 0; i < n; ++i) order[i] = i;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t a, int32_t b) { return scores[a] < scores[b]; });
+    for (int32_t i = 0; i < n; ++i) out_mask[i] = 0;
+    for (int32_t i = 0; i < n_freeze; ++i) out_mask[order[i]] = 1;
+    return TF_OK;
+}
+
+int32_t tf_num_frozen(double r, int32_t n) {
+    if (n <= 0 || !(r > 0.0)) return 0;
+    const double x = std::ceil(r * double(n) - 1e-9);
+    if (x >= double(n)) return n;
+    return x < 0.0 ? 0 : int32_t(x);
+}
+
+}  // extern "C"

@@ -1,0 +1,93 @@
+// Internal declarations shared by the translation units of libtf.so.
+// Host-side launch functions; every one only enqueues on `stream`.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tf {
+
+enum class Dtype : int { F32 = 0, BF16 = 1 };
+
+// ---------------------------------------------------------------------------
+// Grouped GEMM problem: C[M x N] (+)= sum_k A(m,k) * B(n,k), C row-major.
+//   kNT ("rows share the contraction"): A is [M x Kc] row-major, B is [N x Kc]
+//        row-major  ->  the input-gradient product dX = dY * W^T
+//        (A = dY [T x N_l], B = W [K_l x N_l], C = dX [T x K_l]).
+//   kTN ("contraction is the slow dimension"): A is [Kc x M] row-major, B is
+//        [Kc x N] row-major  ->  the weight-gradient product dW = X^T * dY
+//        (A = X [T x K_l], B = dY [T x N_l], C = dW [K_l x N_l]).
+// ---------------------------------------------------------------------------
+enum class Layout : int { kNT = 0, kTN = 1 };
+
+struct GemmProblem {
+    const void* A;
+    const void* B;
+    void* C;
+    int32_t M, N, Kc;
+    int32_t tile_start;     // first tile index of this problem inside a launch
+};
+
+constexpr int kMaxProblemsPerLaunch = 64;
+
+struct GemmBatch {          // passed by value as the kernel argument (< 4 KB)
+    GemmProblem p[kMaxProblemsPerLaunch];
+    int32_t n_problems;
+    int32_t total_tiles;
+};
+
+// Edge-safe LDS-tiled FMA kernel (any M, N, Kc >= 1).  in: fp32 or bf16,
+// accumulate fp32, out: fp32 (optionally +=) or bf16.
+hipError_t launch_gemm_generic(hipStream_t stream, GemmBatch& batch, int n_problems,
+                               Layout layout, Dtype in_dtype, Dtype out_dtype, bool accumulate);
+
+// MFMA kernel for bf16 inputs.  Requires M % 256 == 0, N % 256 == 0, Kc % 64 == 0
+// for every problem in the batch (mfma_shape_ok).
+bool mfma_shape_ok(int64_t M, int64_t N, int64_t Kc);
+hipError_t launch_gemm_mfma_bf16(hipStream_t stream, GemmBatch& batch, int n_problems,
+                                 Layout layout, Dtype out_dtype, bool accumulate);
+int gemm_generic_tile();          // tile edge of the generic kernel (square)
+int gemm_mfma_tile();             // tile edge of the MFMA kernel (square)
+
+// ---------------------------------------------------------------------------
+// Fused elementwise pass: masked AdamW (+ APF EMAs) or the stand-alone EMA
+// update.  One descriptor per unfrozen tensor.
+// ---------------------------------------------------------------------------
+struct EwTensor {
+    float* p;               // fp32 master (adamw) / unused (stability)
+    float* m;
+    float* v;
+    const void* g;          // gradient (adamw) or delta (stability, fp32)
+    uint16_t* p_lowp;       // optional bf16 copy
+    const uint32_t* bits;   // optional element mask, 1 = frozen
+    float* E;               // optional (adamw) / required (stability)
+    float* A;
+    double* sums;           // optional: &score_sums[2*i]
+    int64_t numel;
+    float rbc1, rbc2;       // 1/(1-beta1^t), 1/(1-beta2^t)
+    int32_t block_start;    // first block of this tensor inside a launch
+    int32_t pad_;
+};
+
+constexpr int kMaxTensorsPerLaunch = 32;
+
+struct EwBatch {            // passed by value as the kernel argument (< 4 KB)
+    EwTensor t[kMaxTensorsPerLaunch];
+    int32_t n_tensors;
+    int32_t total_blocks;
+};
+
+struct AdamwParams {
+    float grad_scale;
+    float lr, beta1, beta2, eps, weight_decay;
+    float one_minus_beta1, one_minus_beta2;
+    float ema_decay, one_minus_ema_decay;
+};
+
+int64_t ew_elems_per_block();
+hipError_t launch_adamw(hipStream_t stream, EwBatch& batch, int n_tensors,
+                        const AdamwParams& hp, Dtype grad_dtype);
+hipError_t launch_stability(hipStream_t stream, EwBatch& batch, int n_tensors,
+                            const AdamwParams& hp);
+
+}  // namespace tf
