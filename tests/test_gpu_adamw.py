@@ -63,7 +63,7 @@ def _check(states, frozen_elem, tensor_mask, before_bytes, label=""):
                 b = np.frombuffer(before_bytes[i][k], dtype=np.uint16 if k == "low" else np.uint32)
                 a = np.frombuffer(raw_bytes(s.d[k]), dtype=b.dtype)
                 assert np.array_equal(a[f], b[f]), f"{label} frozen elements of tensor {i} buffer {k} changed"
-                if k != "low":
+                if k != "low" and (~f).sum() > 100:
                     assert np.mean(a[~f] != b[~f]) > 0.99       # the others did move
 
 
