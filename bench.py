@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Benchmark of the freeze-aware stage backward + masked AdamW + APF EMAs on
+one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic microbatch:
+  tf_stage_backward (dX for every layer, dW for unfrozen layers only)
+  -> tf_masked_adamw fused with the stability EMAs and per-tensor score sums
+  -> score sums to host -> tf_stability_scores -> tf_select_lowest.
+The workload is the LLaMA-1B-shaped stage (4 blocks, d=2048, GQA kv=512,
+ffn=8192, 4x2048 tokens, bf16 with fp32 master weights and Adam states); the
+mask freezes the ceil(r*L) tensors with the lowest APF score after 5 seeded
+warm-up optimizer steps.  `value` is tokens/s at r = 0.5; the sweep over r is
+reported in "sweep".  Inputs are seeded and synthetic (workloads.py) and are
+resident in HBM before the timed region starts.
+
+One JSON line is printed on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E
+HEADLINE_R = 0.5
+PAPER_CONTEXT = ("paper: LLaMA-3-8B fine-tuning throughput +36..40% at average freeze ratio ~0.33-0.36, "
+                 "4xH200 NVLink, PP=4, 8 microbatches (Table llama8b) - other hardware, context only")
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3], help="config id (2 = LLaMA-1B-shaped stage)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true")
+    return ap.parse_args()
+
+
+class Stage:
+    """All device buffers of one stage, filled from the seeded generators."""
+
+    def __init__(self, cfg, wl, tf, torch):
+        def dev(a, dtype):
+            if dtype == "bf16":
+                bits = wl.f32_to_bf16_bits(a).view(np.int16)
+                return torch.from_numpy(bits).cuda().view(torch.bfloat16).reshape(a.shape)
+            return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+
+        self.cfg, self.tf, self.torch = cfg, tf, torch
+        self.shapes = cfg.shapes
+        self.L = cfg.n_layers
+        self.T = cfg.T
+        self.sizes = [k * n for k, n in self.shapes]
+        t0 = time.time()
+
+        def make(l):
+            p = wl.gen_weight(cfg, l)
+            _, X, dY = wl.gen_layer(cfg, l)
+            return p, X, dY
+
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            host = list(ex.map(make, range(self.L)))
+        log(f"generated inputs for {self.L} layers in {time.time() - t0:.1f}s")
+        bf, f32 = torch.bfloat16, torch.float32
+        self.p = [dev(h[0].reshape(-1), "f32") for h in host]
+        self.W = [dev(h[0], "bf16") for h in host]                 # stored bf16 copy of the master weights
+        self.X = [dev(h[1], "bf16") for h in host]
+        self.dY = [dev(h[2], "bf16") for h in host]
+        del host
+        z = lambda dt: [torch.zeros(n, dtype=dt, device="cuda") for n in self.sizes]
+        self.m, self.v, self.E, self.A = z(f32), z(f32), z(f32), z(f32)
+        self.dX = [torch.empty((self.T, k), dtype=bf, device="cuda") for k, n in self.shapes]
+        self.dW = [torch.zeros((k, n), dtype=bf, device="cuda") for k, n in self.shapes]
+        self.sums = torch.zeros(2 * self.L, dtype=torch.float64, device="cuda")
+        self.steps = [1] * self.L
+        self.hp = {k: float(np.float32(getattr(cfg, k))) for k in ("lr", "beta1", "beta2", "eps", "weight_decay")}
+        self.decay = float(np.float32(cfg.ema_decay))
+        torch.cuda.synchronize()
+        log(f"device buffers ready, {torch.cuda.memory_allocated() / 2**30:.1f} GiB")
+
+    def adamw(self, ctx, grads, mask):
+        hp = self.hp
+        self.tf.tf_masked_adamw(ctx, self.sizes, self.p, self.m, self.v, grads, self.tf.TF_BF16, self.steps,
+                                hp["lr"], hp["beta1"], hp["beta2"], hp["eps"], hp["weight_decay"],
+                                p_lowp=self.W, tensor_freeze_mask=mask, ema=self.E, ema_abs=self.A,
+                                ema_decay=self.decay, score_sums=self.sums)
+        for l in range(self.L):
+            if mask is None or not mask[l]:
+                self.steps[l] += 1
+
+    def step(self, ctx, mask, n_freeze):
+        """One pass of the hot path; returns the mask the scores would pick next."""
+        tf = self.tf
+        tf.tf_stage_backward(ctx, self.shapes, self.T, tf.TF_BF16, self.W, self.X, self.dY, mask,
+                             self.dX, self.dW, tf.TF_BF16)
+        self.adamw(ctx, self.dW, mask)
+        sums_host = self.sums.cpu().numpy()                      # synchronises the stream
+        scores = tf.tf_stability_scores(sums_host)
+        return tf.tf_select_lowest(scores, n_freeze)
+
+
+def cpu_baseline(cfg, wl, r):
+    """Time the fp64 oracle on a bounded sample of the same workload: block 0's
+    seven layers, the first Ts tokens, backward at ratio r + AdamW/EMA step."""
+    import oracle
+    Ts = 512
+    sub = wl.scaled(cfg, blocks=1)
+    sh = sub.shapes
+    mask = wl.permutation_mask(sub, r)
+    f64 = lambda a: np.ascontiguousarray(a, dtype=np.float64)
+    W, X, dY = zip(*[wl.gen_layer(sub, l, T=Ts) for l in range(7)])
+    W, X, dY = [f64(a) for a in W], [f64(a) for a in X], [f64(a) for a in dY]
+    dX = [np.zeros((Ts, k)) for k, n in sh]
+    dW = [None if mask[l] else np.zeros(sh[l]) for l in range(7)]
+    t0 = time.perf_counter()
+    oracle.stage_backward(sh, Ts, W, X, dY, mask, dX, dW)
+    t_bwd = time.perf_counter() - t0
+    hp = {k: getattr(cfg, k) for k in ("lr", "beta1", "beta2", "eps", "weight_decay")}
+    t_opt = 0.0
+    for l in range(7):
+        if mask[l]:
+            continue
+        n = sh[l][0] * sh[l][1]
+        st = [np.ones(n) * 1e-3 for _ in range(5)]               # touched pages: time the arithmetic, not the faults
+        g = dW[l].reshape(-1)
+        t0 = time.perf_counter()
+        oracle.masked_adamw(st[0], st[1], st[2], g, step=1, ema=st[3], ema_abs=st[4], ema_decay=cfg.ema_decay, **hp)
+        t_opt += time.perf_counter() - t0
+    # one full step = backward over T tokens of all blocks + optimizer over all blocks
+    t_full = t_bwd * (cfg.T / Ts) * cfg.blocks + t_opt * cfg.blocks
+    return {
+        "value": cfg.T / t_full, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"block 0 of {cfg.blocks} (7 layers), first {Ts} of {cfg.T} tokens, r={r} "
+                  f"({int(mask.sum())}/7 tensors frozen): backward {t_bwd:.2f}s + AdamW/EMA {t_opt:.2f}s measured, "
+                  f"scaled by tokens and blocks to a full step of {t_full:.0f}s",
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU's stage; --gpus N with N > 1 is not supported "
+              "(no collectives or sharding are part of this library).", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads as wl
+    import paper_2602_05754_amd as tf
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(tf.library_path()):
+        raise RuntimeError("libtf.so has not been built (python -c 'import __graft_entry__ as g; g.build()')")
+    cfg = wl.CONFIGS[args.workload]
+    torch.cuda.set_device(0)
+    ctx = tf.Context(0)
+    st = Stage(cfg, wl, tf, torch)
+    L, T, P = st.L, st.T, cfg.n_params
+
+    # ---- mask selection: 5 seeded warm-up optimizer steps with nothing frozen, then lowest scores ----
+    t0 = time.time()
+    for s in range(1, 6):
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            grads = list(ex.map(lambda l: wl.f32_to_bf16_bits(wl.gen_grad(cfg, l, s)).view(np.int16), range(L)))
+        gd = [torch.from_numpy(g).cuda().view(torch.bfloat16) for g in grads]
+        st.adamw(ctx, gd, None)
+        torch.cuda.synchronize()
+        del gd, grads
+    scores = tf.tf_stability_scores(st.sums.cpu().numpy())
+    log(f"warm-up optimizer steps done in {time.time() - t0:.1f}s; score range {scores.min():.4f}..{scores.max():.4f}")
+
+    def run(r, steps, warmup):
+        n = tf.tf_num_frozen(r, L)
+        mask = tf.tf_select_lowest(scores, n)
+        phi = wl.frozen_param_fraction(cfg, mask)
+        for _ in range(warmup):
+            st.step(ctx, mask, n)
+        torch.cuda.synchronize()
+        ctx.profile_enable(True)
+        ctx.profile_collect()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            st.step(ctx, mask, n)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        prof = ctx.profile_collect()
+        ctx.profile_enable(False)
+        per_kind = {}
+        for k, ms in prof:
+            per_kind.setdefault(k, []).append(ms)
+        kern = {k: {"launches_per_step": len(v) / steps, "avg_ms": float(np.mean(v))} for k, v in per_kind.items()}
+        ms_step = dt / steps * 1e3
+        flops = 2.0 * T * P * (2.0 - phi)
+        unfrozen = sum(st.sizes[l] for l in range(L) if not mask[l])
+        out = {"r": r, "n_frozen": int(n), "phi": phi, "ms_per_step": ms_step, "tokens_per_s": T / (ms_step / 1e3),
+               "tflops": flops / (ms_step / 1e3) / 1e12, "kernels": kern}
+        g_ms = sum(v["avg_ms"] * v["launches_per_step"] for k, v in kern.items() if k.startswith("d"))
+        out["backward_ms"] = g_ms
+        out["backward_tflops"] = flops / (g_ms / 1e3) / 1e12 if g_ms > 0 else None
+        out["backward_pct_mfma_peak"] = 100.0 * out["backward_tflops"] / PEAK_BF16_TFLOPS if g_ms > 0 else None
+        if "adamw" in kern:
+            a_ms = kern["adamw"]["avg_ms"] * kern["adamw"]["launches_per_step"]
+            out["adamw_ms"] = a_ms
+            out["adamw_gbps"] = 44.0 * unfrozen / (a_ms / 1e3) / 1e9
+            out["adamw_pct_hbm_peak"] = 100.0 * out["adamw_gbps"] / PEAK_HBM_GBPS
+        return out, mask
+
+    head, head_mask = run(HEADLINE_R, args.steps, args.warmup)
+    log(f"r={HEADLINE_R}: {head['ms_per_step']:.3f} ms/step, {head['tokens_per_s']:.0f} tok/s, "
+        f"backward {head['backward_tflops']:.0f} TFLOP/s")
+    sweep = []
+    if not args.no_sweep:
+        for r in wl.R_SWEEP[cfg.cfg_id] + [1.0]:
+            s, _ = run(r, args.steps, 2) if r != HEADLINE_R else (head, None)
+            sweep.append(s)
+            log(f"sweep r={r}: phi={s['phi']:.3f} {s['ms_per_step']:.3f} ms/step, backward {s['backward_ms']:.3f} ms")
+        t_by_r = {s["r"]: s for s in sweep}
+        if 0.0 in t_by_r and 1.0 in t_by_r:
+            b0, b1 = t_by_r[0.0]["backward_ms"], t_by_r[1.0]["backward_ms"]
+            for s in sweep:
+                if 0.0 < s["r"] < 1.0 and s["phi"] > 0:
+                    # time saved relative to what the skipped dW FLOP fraction would ideally save
+                    s["eta_backward"] = (b0 - s["backward_ms"]) / (s["phi"] * (b0 - b1))
+
+    # ---- roofline of the dominant kernel: the grouped input-gradient GEMM ----
+    dx = head["kernels"].get("dx_mfma")
+    roofline = None
+    if dx:
+        fl = 2.0 * T * P / dx["launches_per_step"]
+        ach = fl / (dx["avg_ms"] / 1e3) / 1e12
+        roofline = {"kernel": "gemm_mfma_kernel<NT> (dX = dY W^T, all layers, one grouped launch)",
+                    "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": read_traffic("dx_mfma", cfg.cfg_id),
+                    "avg_launch_ms": dx["avg_ms"], "flop_per_launch": fl}
+    extra = {}
+    dw = head["kernels"].get("dw_mfma")
+    if dw:
+        fl = 2.0 * T * P * (1.0 - head["phi"]) / dw["launches_per_step"]
+        ach = fl / (dw["avg_ms"] / 1e3) / 1e12
+        extra["roofline_dw"] = {"kernel": "gemm_mfma_kernel<TN> (dW = X^T dY, unfrozen layers only)", "bound": "mfma",
+                                "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                                "frac": ach / PEAK_BF16_TFLOPS, "traffic": read_traffic("dw_mfma", cfg.cfg_id),
+                                "avg_launch_ms": dw["avg_ms"]}
+    if "adamw_gbps" in head:
+        extra["roofline_adamw"] = {"kernel": "ew_kernel (masked AdamW + APF EMAs + score sums)", "bound": "hbm",
+                                   "achieved": head["adamw_gbps"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                   "frac": head["adamw_gbps"] / PEAK_HBM_GBPS,
+                                   "traffic": read_traffic("adamw", cfg.cfg_id), "avg_launch_ms": head["adamw_ms"]}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        log("timing the fp64 oracle on a bounded sample (host cores)...")
+        cpu = cpu_baseline(cfg, wl, HEADLINE_R)
+        log(f"oracle: {cpu['value']:.2f} tokens/s on {cpu['cores']} threads")
+
+    line = {
+        "metric": f"stage-backward tokens/s (freeze-aware backward + masked AdamW + APF EMAs), r={HEADLINE_R}",
+        "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg{cfg.cfg_id} {cfg.name}: {cfg.blocks} blocks, d={cfg.d}, kv={cfg.kv}, ffn={cfg.ffn}, "
+                               f"T={cfg.T} tokens, L={L} tensors, P={P} params",
+                   "r": HEADLINE_R, "n_frozen": head["n_frozen"], "phi": head["phi"],
+                   "mask": "ceil(r*L) lowest APF scores after 5 seeded warm-up steps"},
+        "tflops": head["tflops"], "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep,
+        "paper_context": PAPER_CONTEXT,
+    }
+    line.update(extra)
+    ctx.close()
+    print(json.dumps(line), flush=True)
+
+
+def read_traffic(kernel: str, cfg_id: int):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), as
+    recorded in profiles/hbm_traffic.txt ("<kernel> cfg<id> <bytes>"), or None."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for ln in open(path):
+        f = ln.split()
+        if len(f) >= 3 and not ln.startswith("#") and f[0] == kernel and f[1] == f"cfg{cfg_id}":
+            return float(f[2])
+    return None
+
+
+if __name__ == "__main__":
+    main()

@@ -74,6 +74,26 @@ const char* tf_strerror(int code);
 /* Raw hipError_t of the most recent TF_ERR_HIP on this context (0 if none). */
 int tf_last_hip_error(const tf_ctx* ctx);
 
+/*
+ * Optional per-kernel timing (the analogue of the paper's monitoring of action
+ * times, Sec. 3.1, at kernel granularity).  While enabled, every kernel the
+ * library launches is bracketed by a HIP event pair recorded on the launch
+ * stream.  tf_profile_collect waits for the recorded events, writes up to
+ * `capacity` (kind, milliseconds) pairs in launch order into the HOST arrays
+ * `kinds` and `ms`, stores the count in *n_out and forgets all records.
+ * Disabled by default; costs nothing when disabled.
+ */
+typedef enum {
+    TF_KERNEL_DX_MFMA = 0,      /* input-gradient GEMMs on the matrix cores   */
+    TF_KERNEL_DW_MFMA = 1,      /* weight-gradient GEMMs on the matrix cores  */
+    TF_KERNEL_DX_GENERIC = 2,   /* input-gradient GEMMs, fp32-FMA kernel      */
+    TF_KERNEL_DW_GENERIC = 3,   /* weight-gradient GEMMs, fp32-FMA kernel     */
+    TF_KERNEL_ADAMW = 4,        /* fused masked AdamW (+ stability EMAs)      */
+    TF_KERNEL_STABILITY = 5     /* stand-alone stability update               */
+} tf_kernel_kind;
+int tf_profile_enable(tf_ctx* ctx, int enable);
+int tf_profile_collect(tf_ctx* ctx, int32_t capacity, int32_t* kinds, float* ms, int32_t* n_out);
+
 /* Library version, "major.minor.patch". */
 const char* tf_version(void);
 

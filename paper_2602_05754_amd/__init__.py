@@ -6,5 +6,5 @@ or PyTorch fallback: without the built library, calls raise."""
 from .binding import (  # noqa: F401
     TF_BF16, TF_F32, Context, TfError, library_path, load_library,
     tf_masked_adamw, tf_num_frozen, tf_select_lowest, tf_stability_scores,
-    tf_stability_update, tf_stage_backward, tf_strerror, tf_version, EXPORTED_SYMBOLS,
+    tf_stability_update, tf_stage_backward, tf_strerror, tf_version, EXPORTED_SYMBOLS, KERNEL_KINDS,
 )

@@ -20,7 +20,10 @@ EXPORTED_SYMBOLS = [
     "tf_create", "tf_destroy", "tf_strerror", "tf_last_hip_error", "tf_version",
     "tf_stage_backward", "tf_masked_adamw", "tf_stability_update",
     "tf_stability_scores", "tf_select_lowest", "tf_num_frozen",
+    "tf_profile_enable", "tf_profile_collect",
 ]
+
+KERNEL_KINDS = {0: "dx_mfma", 1: "dw_mfma", 2: "dx_generic", 3: "dw_generic", 4: "adamw", 5: "stability"}
 
 
 class TfError(RuntimeError):
@@ -73,6 +76,10 @@ def load_library():
     lib.tf_select_lowest.argtypes = [vp, i32, i32, vp]
     lib.tf_num_frozen.restype = i32
     lib.tf_num_frozen.argtypes = [f64, i32]
+    lib.tf_profile_enable.restype = ctypes.c_int
+    lib.tf_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.tf_profile_collect.restype = ctypes.c_int
+    lib.tf_profile_collect.argtypes = [vp, i32, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -159,6 +166,22 @@ class Context:
 
     def last_hip_error(self) -> int:
         return int(load_library().tf_last_hip_error(self._h))
+
+    def profile_enable(self, on: bool = True) -> None:
+        rc = load_library().tf_profile_enable(self._h, 1 if on else 0)
+        if rc != 0:
+            raise TfError(rc, "tf_profile_enable")
+
+    def profile_collect(self, capacity: int = 4096):
+        """[(kernel kind name, milliseconds)] of the launches since the last collect."""
+        kinds = np.zeros(capacity, dtype=np.int32)
+        ms = np.zeros(capacity, dtype=np.float32)
+        n = ctypes.c_int32(0)
+        rc = load_library().tf_profile_collect(self._h, capacity, kinds.ctypes.data, ms.ctypes.data,
+                                               ctypes.addressof(n))
+        if rc != 0:
+            raise TfError(rc, "tf_profile_collect", self.last_hip_error() if rc == -6 else 0)
+        return [(KERNEL_KINDS.get(int(k), str(int(k))), float(t)) for k, t in zip(kinds[: n.value], ms[: n.value])]
 
     def close(self):
         if self._h is not None and self._h.value:

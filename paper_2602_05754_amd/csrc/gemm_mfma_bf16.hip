@@ -8,10 +8,16 @@
 // One 256 x 256 output tile per 256-thread workgroup (4 wave64s in a 2 x 2
 // grid, 128 x 128 per wave = 4 x 4 MFMA 32x32x16 tiles, 256 fp32 accumulators
 // per lane).  The contraction advances 64 at a time through two LDS stages of
-// 64 KB.  Both layouts put their operands into LDS in the same form,
-// [row][64 contraction values] with the eight 16-byte chunks of a row XOR-
-// swizzled, so the MFMA loop is shared; kTN transposes 8 x 8 blocks in
-// registers on the way in.
+// 64 KB that are filled by direct global->LDS loads (no register staging):
+// while the matrix cores work on one stage the next one is in flight.
+//
+//   kNT stage: [256 rows][64 contraction] per operand, 16-byte chunks of a row
+//              XOR-swizzled; MFMA operands are plain 128-bit LDS reads.
+//   kTN stage: [64 contraction][256 rows] per operand (the layout in memory),
+//              64-byte blocks of a row XOR-swizzled; MFMA operands come from the
+//              LDS transpose read (4 contraction values of one row per lane).
+// A direct-to-LDS load writes lane i's 16 bytes at (wave-uniform base) + 16 i,
+// so a swizzle is applied by choosing which global address each lane fetches.
 #include "tf_internal.h"
 
 namespace tf {
@@ -19,8 +25,7 @@ namespace {
 
 constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kThreads = 256;
-constexpr int kRowBytes = kBK * 2;                    // 128 B of contraction per tile row
-constexpr int kTileBytes = kBM * kRowBytes;           // 32 KB per operand per stage
+constexpr int kTileBytes = kBM * kBK * 2;             // 32 KB per operand per stage
 constexpr int kStageBytes = 2 * kTileBytes;           // A + B
 constexpr int kLdsBytes = 2 * kStageBytes;            // two stages = 128 KB
 constexpr int kGroupM = 8;                            // tile rows per L2 locality group
@@ -28,75 +33,20 @@ constexpr int kXcds = 8;
 constexpr int kXcdRun = 32;                           // consecutive logical tiles kept on one XCD
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
-struct alignas(16) U4 { uint32_t x, y, z, w; };
-struct alignas(8) U2 { uint32_t x, y; };
-struct alignas(16) F4 { float x, y, z, w; };
+typedef uint32_t U2 __attribute__((ext_vector_type(2)));
+typedef float F4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) bf16x4* LdsBf16x4Ptr;
 
-// 16-byte chunk c (0..7) of tile row `row` lives at chunk c ^ swz(row).  Rows r..r+7
-// (MFMA reads) and rows 8q+j for q..q+7 (transposing writes) both spread over all 8 chunks.
-__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
+#define TF_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define TF_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 __device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
     uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
     a = ((a & 0x7fffffffu) > 0x7f800000u) ? ((a >> 16) | 0x40u) : ((a + 0x7fffu + ((a >> 16) & 1u)) >> 16);
     b = ((b & 0x7fffffffu) > 0x7f800000u) ? ((b >> 16) | 0x40u) : ((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
     return (a & 0xffffu) | (b << 16);
-}
-
-// ---- global -> registers -------------------------------------------------------------------
-// kNT: src is [rows x Kc]; thread reads chunk (tid % 8) of rows tid/8 + 32 p.
-__device__ __forceinline__ void gload_nt(const uint16_t* src, int64_t ld, int row0, int k0, U4 (&r)[8]) {
-    const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
-    const uint16_t* base = src + int64_t(row0 + rr) * ld + k0 + c * 8;
-#pragma unroll
-    for (int p = 0; p < 8; ++p) r[p] = *reinterpret_cast<const U4*>(base + int64_t(32 * p) * ld);
-}
-__device__ __forceinline__ void lstore_nt(char* tile, const U4 (&r)[8]) {
-    const int c = threadIdx.x & 7, rr = threadIdx.x >> 3;
-#pragma unroll
-    for (int p = 0; p < 8; ++p) {
-        const int row = rr + 32 * p;
-        *reinterpret_cast<U4*>(tile + row * kRowBytes + ((c ^ swz(row)) << 4)) = r[p];
-    }
-}
-
-// kTN: src is [Kc x rows]; thread reads 8 consecutive rows-of-the-tile (one 16-byte chunk)
-// at contraction indices k0 + 8 tg + j, j = 0..7, with tg = tid / 32, chunk mc = tid % 32.
-__device__ __forceinline__ void gload_tn(const uint16_t* src, int64_t ld, int row0, int k0, U4 (&r)[8]) {
-    const int mc = threadIdx.x & 31, tg = threadIdx.x >> 5;
-    const uint16_t* base = src + int64_t(k0 + tg * 8) * ld + row0 + mc * 8;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) r[j] = *reinterpret_cast<const U4*>(base + int64_t(j) * ld);
-}
-__device__ __forceinline__ void lstore_tn(char* tile, const U4 (&r)[8]) {
-    const int mc = threadIdx.x & 31, tg = threadIdx.x >> 5;
-    // 8 x 8 transpose of 16-bit values: r[j] holds 8 tile rows at contraction j;
-    // o[i] holds 8 contraction values of tile row i.
-    const uint32_t* in = reinterpret_cast<const uint32_t*>(&r[0]);   // in[j*4 + d]
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        uint32_t o[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const uint32_t a = in[(2 * q) * 4 + (i >> 1)], b = in[(2 * q + 1) * 4 + (i >> 1)];
-            o[q] = (i & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
-        }
-        const int row = mc * 8 + i;
-        *reinterpret_cast<U4*>(tile + row * kRowBytes + ((tg ^ swz(row)) << 4)) = U4{o[0], o[1], o[2], o[3]};
-    }
-}
-
-template <bool kTN>
-__device__ __forceinline__ void gload(const uint16_t* A, const uint16_t* B, int64_t lda, int64_t ldb,
-                                      int m0, int n0, int k0, U4 (&ra)[8], U4 (&rb)[8]) {
-    if (kTN) { gload_tn(A, lda, m0, k0, ra); gload_tn(B, ldb, n0, k0, rb); }
-    else     { gload_nt(A, lda, m0, k0, ra); gload_nt(B, ldb, n0, k0, rb); }
-}
-template <bool kTN>
-__device__ __forceinline__ void lstore(char* stage, const U4 (&ra)[8], const U4 (&rb)[8]) {
-    if (kTN) { lstore_tn(stage, ra); lstore_tn(stage + kTileBytes, rb); }
-    else     { lstore_nt(stage, ra); lstore_nt(stage + kTileBytes, rb); }
 }
 
 // blockIdx -> logical tile.  Hardware hands workgroup b to XCD b % 8; runs of kXcdRun
@@ -110,9 +60,138 @@ __device__ __forceinline__ int logical_tile(int b, int nb) {
     return ((idx / kXcdRun) * kXcds + xcd) * kXcdRun + idx % kXcdRun;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Stage fill.  Each wave issues 8 direct-to-LDS loads per operand; load p of wave w fills the
+// 1 KB of the operand tile at (4 p + w) KB.
+//   kNT: that KB is tile rows R = 32 p + 8 w + lane/8, physical chunk lane%8 of each row;
+//        logical chunk = physical ^ ((R ^ (R >> 3)) & 7).
+//   kTN: that KB is contraction rows T = 8 p + 2 w + lane/32, 16-byte slot lane%32 of each;
+//        logical 64-byte block = physical block ^ (T & 3).
+// ---------------------------------------------------------------------------------------------
+struct FillPtrs {
+    const char* a[2];         // per-lane global byte pointers of load p = 0 (and p = 1 for kNT)
+    const char* b[2];
+    int64_t step_a, step_b;   // byte distance between loads p and p + 2 (kNT) / p and p + 1 (kTN)
+};
+
+template <bool kTN>
+__device__ __forceinline__ FillPtrs make_fill(const uint16_t* A, const uint16_t* B, int64_t lda, int64_t ldb,
+                                              int m0, int n0) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    FillPtrs f;
+    if (kTN) {
+        const int T = 2 * w + (lane >> 5);                     // + 8 p
+        const int slot = lane & 31;
+        const int blk = (slot >> 2) ^ (T & 3);
+        const int col = blk * 32 + (slot & 3) * 8;             // element offset inside the 256-wide tile row
+        f.a[0] = reinterpret_cast<const char*>(A + int64_t(T) * lda + m0 + col);
+        f.b[0] = reinterpret_cast<const char*>(B + int64_t(T) * ldb + n0 + col);
+        f.a[1] = f.a[0]; f.b[1] = f.b[0];
+        f.step_a = 8 * lda * 2; f.step_b = 8 * ldb * 2;
+    } else {
+        const int r = 8 * w + (lane >> 3);                     // + 32 p
+        const int pc = lane & 7;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {                          // p even / odd differ in bit 2 of the swizzle
+            const int R = r + 32 * q;
+            const int c = pc ^ ((R ^ (R >> 3)) & 7);
+            f.a[q] = reinterpret_cast<const char*>(A + int64_t(m0 + R) * lda + c * 8);
+            f.b[q] = reinterpret_cast<const char*>(B + int64_t(n0 + R) * ldb + c * 8);
+        }
+        f.step_a = 64 * lda * 2; f.step_b = 64 * ldb * 2;
+    }
+    return f;
+}
+
+// One direct-to-LDS load: every lane fetches 16 bytes from its own global address and the
+// wave's 1 KB lands at LDS byte address lds_base (wave-uniform, goes through M0) + 16 * lane.
+// Written as inline assembly so that the compiler's wait-count insertion does not treat every
+// later LDS read as dependent on it (it would drain the load queue before each transpose read);
+// completion is awaited explicitly with wait_direct_loads() before the stage barrier.
+__device__ __forceinline__ void direct_load_16B(const char* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_base), "v"(gptr)
+                 : "memory");
+}
+__device__ __forceinline__ void wait_direct_loads() {
+    __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0), other counters untouched
+}
+
+// Issue load number q (0..15) of a stage fill: even q fetch operand A, odd q operand B, load p = q / 2.
+template <bool kTN>
+__device__ __forceinline__ void fill_one(const FillPtrs& f, int64_t koff_a, int64_t koff_b, uint32_t stage_lds, int q) {
+    const uint32_t w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int p = q >> 1;
+    if ((q & 1) == 0) {
+        const char* ga = kTN ? f.a[0] + koff_a + p * f.step_a : f.a[p & 1] + koff_a + (p >> 1) * f.step_a;
+        direct_load_16B(ga, stage_lds + w * 1024 + p * 4096);
+    } else {
+        const char* gb = kTN ? f.b[0] + koff_b + p * f.step_b : f.b[p & 1] + koff_b + (p >> 1) * f.step_b;
+        direct_load_16B(gb, stage_lds + kTileBytes + w * 1024 + p * 4096);
+    }
+}
+
+template <bool kTN>
+__device__ __forceinline__ void fill_stage(const FillPtrs& f, int64_t koff_a, int64_t koff_b, uint32_t stage) {
+#pragma unroll
+    for (int q = 0; q < 16; ++q) fill_one<kTN>(f, koff_a, koff_b, stage, q);
+}
+
+// ---------------------------------------------------------------------------------------------
+// MFMA operand fetch for contraction step s (16 values) of the current stage.
+// Operand lane l holds row (l % 32) of a 32-row block and contraction values 8 (l / 32) .. + 7.
+// ---------------------------------------------------------------------------------------------
+struct FragAddr {
+    int a[4], b[4];       // per-lane LDS byte offsets (inside a stage) of the 4 row blocks, step 0
+};
+
+template <bool kTN>
+__device__ __forceinline__ FragAddr make_frag_addr(int wm, int wn) {
+    const int lane = threadIdx.x & 63;
+    FragAddr fa;
+    if (kTN) {
+        // 16-lane group G reads rows 8 (G / 2) + {0..3} (+4 for the second read) of the
+        // contraction and columns 16 (G % 2) + {0..15} of the 32-row block; as a source lane
+        // ii of its group it fetches row ii / 4, columns 4 (ii % 4) .. + 3.
+        const int G = lane >> 4, ii = lane & 15;
+        const int x = ii >> 2;
+        const int laneoff = (8 * (G >> 1) + x) * 512 + 32 * (G & 1) + 8 * (ii & 3);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            fa.a[i] = laneoff + wm * 256 + ((i ^ x) * 64);
+            fa.b[i] = kTileBytes + laneoff + wn * 256 + ((i ^ x) * 64);
+        }
+    } else {
+        const int lrow = lane & 31, lhalf = lane >> 5;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int ra = wm * 128 + i * 32 + lrow, rb = wn * 128 + i * 32 + lrow;
+            // chunk (2 s + lhalf) ^ swz(row): the s-dependent part is XORed in at use
+            fa.a[i] = ra * 128 + ((lhalf ^ ((ra ^ (ra >> 3)) & 7)) << 4);
+            fa.b[i] = kTileBytes + rb * 128 + ((lhalf ^ ((rb ^ (rb >> 3)) & 7)) << 4);
+        }
+    }
+    return fa;
+}
+
+template <bool kTN>
+__device__ __forceinline__ bf16x8 load_frag(const char* stage, int addr, int s) {
+    if (kTN) {
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            (LdsBf16x4Ptr)TF_LPTR(stage + addr + (16 * s) * 512));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
+            (LdsBf16x4Ptr)TF_LPTR(stage + addr + (16 * s + 4) * 512));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    } else {
+        // chunk index 2 s + lhalf, swizzled: 2 s only touches bits 1..2 of the chunk, lhalf bit 0
+        return *reinterpret_cast<const bf16x8*>(stage + (addr ^ (s << 5)));
+    }
+}
+
 template <bool kTN, bool kOutBf16, bool kAccumulate>
 __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
 
     const int lt = logical_tile(blockIdx.x, gridDim.x);
     int pi = 0;
@@ -132,10 +211,12 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     const uint16_t* A = static_cast<const uint16_t*>(P.A);
     const uint16_t* B = static_cast<const uint16_t*>(P.B);
     const int64_t lda = kTN ? M : Kc, ldb = kTN ? N : Kc;
+    // byte advance of the global pointers per contraction step of 64
+    const int64_t kstep_a = kTN ? int64_t(kBK) * lda * 2 : kBK * 2;
+    const int64_t kstep_b = kTN ? int64_t(kBK) * ldb * 2 : kBK * 2;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
-    const int lrow = lane & 31, lhalf = lane >> 5;
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -145,44 +226,59 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    U4 ra[8], rb[8];
+    const FillPtrs fp = make_fill<kTN>(A, B, lda, ldb, m0, n0);
+    const FragAddr fr = make_frag_addr<kTN>(wm, wn);
     const int nk = Kc / kBK;
-    gload<kTN>(A, B, lda, ldb, m0, n0, 0, ra, rb);
-    lstore<kTN>(lds, ra, rb);
-    __syncthreads();
+
+    // LDS byte address of the dynamic shared array (a 32-bit LDS pointer is its byte offset)
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
+        uint32_t(reinterpret_cast<uintptr_t>(TF_LPTR(lds))));
+    fill_stage<kTN>(fp, 0, 0, lds_base);
+    wait_direct_loads();
+    __syncthreads();                      // this wave's loads have landed, now everyone else's too
 
     for (int kt = 0; kt < nk; ++kt) {
-        char* cur = lds + (kt & 1) * kStageBytes;
-        char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
-        const bool more = kt + 1 < nk;
-        if (more) gload<kTN>(A, B, lda, ldb, m0, n0, (kt + 1) * kBK, ra, rb);
+        const char* cur = lds + (kt & 1) * kStageBytes;
+        const uint32_t nxt = lds_base + ((kt + 1) & 1) * kStageBytes;
+        // The last step has nothing left to fetch; it re-fetches its own tile into the stage
+        // nobody reads any more, which keeps the loop body one straight-line block.
+        const int kn = min(kt + 1, nk - 1);
+        const int64_t koff_a = kn * kstep_a, koff_b = kn * kstep_b;
 
-        const char* tA = cur + (wm * 128 + lrow) * kRowBytes;
-        const char* tB = cur + kTileBytes + (wn * 128 + lrow) * kRowBytes;
+        // Issue order is pinned with scheduling fences: operands of step 0, then every MFMA of
+        // step s is followed by one operand read of step s + 1 and, in step 0, by one
+        // direct-to-LDS load of the next stage, so LDS and memory latency hide behind the
+        // matrix cores.
+        bf16x8 fa[2][4], fb[2][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            fa[0][i] = load_frag<kTN>(cur, fr.a[i], 0);
+            fb[0][i] = load_frag<kTN>(cur, fr.b[i], 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < kBK / 16; ++s) {
-            bf16x8 fa[4], fb[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int rowa = wm * 128 + i * 32 + lrow, rowb = wn * 128 + i * 32 + lrow;
-                fa[i] = *reinterpret_cast<const bf16x8*>(tA + i * 32 * kRowBytes + (((2 * s + lhalf) ^ swz(rowa)) << 4));
-                fb[i] = *reinterpret_cast<const bf16x8*>(tB + i * 32 * kRowBytes + (((2 * s + lhalf) ^ swz(rowb)) << 4));
+            for (int q = 0; q < 16; ++q) {
+                const int i = q >> 2, j = q & 3;
+                // D rows <- n (B operand rows), D columns <- m: a lane then owns 4 consecutive n
+                // of one output row m, i.e. 4 contiguous elements of row-major C.
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s & 1][j], fa[s & 1][i], acc[i][j], 0, 0, 0);
+                if (s + 1 < kBK / 16 && q < 8) {
+                    if (q & 1) fb[(s + 1) & 1][q >> 1] = load_frag<kTN>(cur, fr.b[q >> 1], s + 1);
+                    else       fa[(s + 1) & 1][q >> 1] = load_frag<kTN>(cur, fr.a[q >> 1], s + 1);
+                }
+                if (s == 0) fill_one<kTN>(fp, koff_a, koff_b, nxt, q);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            // D rows <- n (B operand rows), D columns <- m: a lane then owns 4 consecutive n
-            // of one output row m, i.e. 4 contiguous elements of row-major C.
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
         }
-
-        if (more) lstore<kTN>(nxt, ra, rb);
-        __syncthreads();
+        wait_direct_loads();
+        __syncthreads();                  // next stage landed everywhere, this one is free to overwrite
     }
 
     // epilogue: acc[i][j][4g + e] is C[m][n] with m = m0 + wm*128 + i*32 + lane%32,
     // n = n0 + wn*128 + j*32 + 8g + 4*(lane/32) + e.
+    const int lrow = lane & 31, lhalf = lane >> 5;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int64_t m = m0 + wm * 128 + i * 32 + lrow;

@@ -10,9 +10,17 @@
 #include <new>
 #include <vector>
 
+struct tf_prof_rec {
+    int kind;
+    hipEvent_t start, stop;
+};
+
 struct tf_ctx {
     int device_id;
     int last_hip_error;
+    bool profiling;
+    std::vector<tf_prof_rec> recs;      // events recorded since the last tf_profile_collect
+    std::vector<hipEvent_t> pool;       // events ready for reuse
 };
 
 namespace {
@@ -28,6 +36,28 @@ int hip_fail(tf_ctx* ctx, hipError_t e) {
     return TF_ERR_HIP;
 }
 
+// Optional per-kernel timing: a start/stop event pair around one launch, on the launch stream.
+struct ProfScope {
+    tf_ctx* ctx;
+    hipStream_t stream;
+    tf_prof_rec rec;
+    bool on;
+    ProfScope(tf_ctx* c, hipStream_t s, int kind) : ctx(c), stream(s), on(c->profiling) {
+        if (!on) return;
+        rec.kind = kind;
+        for (hipEvent_t* e : {&rec.start, &rec.stop}) {
+            if (!ctx->pool.empty()) { *e = ctx->pool.back(); ctx->pool.pop_back(); }
+            else if (hipEventCreate(e) != hipSuccess) { on = false; return; }
+        }
+        (void)hipEventRecord(rec.start, stream);
+    }
+    ~ProfScope() {
+        if (!on) return;
+        (void)hipEventRecord(rec.stop, stream);
+        ctx->recs.push_back(rec);
+    }
+};
+
 // One planned GEMM: which layer, as which problem.
 struct Planned {
     const void* A;
@@ -38,7 +68,7 @@ struct Planned {
 
 // Launch `items` in batches of at most kMaxProblemsPerLaunch, MFMA-eligible ones on the
 // matrix cores, the rest on the generic kernel.
-hipError_t launch_planned(hipStream_t stream, std::vector<Planned>& items, Layout layout,
+hipError_t launch_planned(tf_ctx* ctx, hipStream_t stream, std::vector<Planned>& items, Layout layout,
                           Dtype in_dtype, Dtype out_dtype, bool accumulate) {
     std::vector<Planned> fast, slow;
     for (const Planned& it : items) {
@@ -70,6 +100,8 @@ hipError_t launch_planned(hipStream_t stream, std::vector<Planned>& items, Layou
                 ++n; ++i;
             }
             batch.total_tiles = int32_t(tiles);
+            const int kind = (layout == Layout::kNT ? TF_KERNEL_DX_MFMA : TF_KERNEL_DW_MFMA) + (pass == 0 ? 0 : 2);
+            ProfScope prof(ctx, stream, kind);
             const hipError_t e = pass == 0
                 ? launch_gemm_mfma_bf16(stream, batch, n, layout, out_dtype, accumulate)
                 : launch_gemm_generic(stream, batch, n, layout, in_dtype, out_dtype, accumulate);
@@ -139,14 +171,43 @@ int tf_create(tf_ctx** out, int device_id) {
     if (!ctx) return TF_ERR_WORKSPACE;
     ctx->device_id = device_id;
     ctx->last_hip_error = 0;
+    ctx->profiling = false;
     *out = ctx;
     return TF_OK;
 }
 
 int tf_destroy(tf_ctx* ctx) {
     if (!ctx) return TF_ERR_INVALID_ARG;
+    for (tf_prof_rec& r : ctx->recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    for (hipEvent_t e : ctx->pool) (void)hipEventDestroy(e);
     delete ctx;
     return TF_OK;
+}
+
+int tf_profile_enable(tf_ctx* ctx, int enable) {
+    if (!ctx || (enable != 0 && enable != 1)) return TF_ERR_INVALID_ARG;
+    ctx->profiling = enable != 0;
+    return TF_OK;
+}
+
+int tf_profile_collect(tf_ctx* ctx, int32_t capacity, int32_t* kinds, float* ms, int32_t* n_out) {
+    if (!ctx || !n_out || capacity < 0 || (capacity > 0 && (!kinds || !ms))) return TF_ERR_INVALID_ARG;
+    int32_t n = 0;
+    int rc = TF_OK;
+    for (tf_prof_rec& r : ctx->recs) {
+        if (n < capacity && rc == TF_OK) {
+            hipError_t e = hipEventSynchronize(r.stop);
+            float t = 0.f;
+            if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
+            if (e != hipSuccess) rc = hip_fail(ctx, e);
+            else { kinds[n] = r.kind; ms[n] = t; ++n; }
+        }
+        ctx->pool.push_back(r.start);
+        ctx->pool.push_back(r.stop);
+    }
+    ctx->recs.clear();
+    *n_out = n;
+    return rc;
 }
 
 int tf_last_hip_error(const tf_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
@@ -195,7 +256,7 @@ int tf_stage_backward(tf_ctx* ctx, void* hip_stream,
     plan.reserve(n_layers);
     for (int32_t l = 0; l < n_layers; ++l)
         plan.push_back(Planned{dY[l], W[l], dX[l], T, shapes[l].K, shapes[l].N});
-    hipError_t e = launch_planned(stream, plan, Layout::kNT, in_dt, in_dt, false);
+    hipError_t e = launch_planned(ctx, stream, plan, Layout::kNT, in_dt, in_dt, false);
     if (e != hipSuccess) return hip_fail(ctx, e);
 
     // weight gradients: unfrozen layers only; a frozen layer is simply not in the plan
@@ -204,7 +265,7 @@ int tf_stage_backward(tf_ctx* ctx, void* hip_stream,
         if (freeze_mask && freeze_mask[l]) continue;
         plan.push_back(Planned{X[l], dY[l], dW[l], shapes[l].K, shapes[l].N, T});
     }
-    e = launch_planned(stream, plan, Layout::kTN, in_dt, to_dtype(dw_dtype), accumulate != 0);
+    e = launch_planned(ctx, stream, plan, Layout::kTN, in_dt, to_dtype(dw_dtype), accumulate != 0);
     if (e != hipSuccess) return hip_fail(ctx, e);
     return TF_OK;
 }
@@ -256,6 +317,7 @@ int tf_masked_adamw(tf_ctx* ctx, void* hip_stream,
     int64_t blocks = 0;
     auto flush = [&]() -> hipError_t {
         batch.total_blocks = int32_t(blocks);
+        ProfScope prof(ctx, stream, TF_KERNEL_ADAMW);
         const hipError_t e = launch_adamw(stream, batch, n, hp, to_dtype(grad_dtype));
         n = 0; blocks = 0;
         return e;
@@ -325,6 +387,7 @@ int tf_stability_update(tf_ctx* ctx, void* hip_stream,
     int64_t blocks = 0;
     auto flush = [&]() -> hipError_t {
         batch.total_blocks = int32_t(blocks);
+        ProfScope prof(ctx, stream, TF_KERNEL_STABILITY);
         const hipError_t e = launch_stability(stream, batch, n, hp);
         n = 0; blocks = 0;
         return e;
