@@ -9,7 +9,11 @@
 // grid, 128 x 128 per wave = 4 x 4 MFMA 32x32x16 tiles, 256 fp32 accumulators
 // per lane).  The contraction advances 64 at a time through two LDS stages of
 // 64 KB that are filled by direct global->LDS loads (no register staging):
-// while the matrix cores work on one stage the next one is in flight.
+// while the matrix cores work on one stage the next one is in flight.  A stage
+// is consumed in four steps of 16; the operands of step s + 1 are read from LDS
+// while the MFMAs of step s issue, the stage barrier sits after the reads of the
+// last step, and the first operands of the next stage are read during the last
+// step, so neither LDS latency nor the barrier leaves the matrix cores idle.
 //
 //   kNT stage: [256 rows][64 contraction] per operand, 16-byte chunks of a row
 //              XOR-swizzled; MFMA operands are plain 128-bit LDS reads.
@@ -31,6 +35,14 @@ constexpr int kLdsBytes = 2 * kStageBytes;            // two stages = 128 KB
 constexpr int kGroupM = 8;                            // tile rows per L2 locality group
 constexpr int kXcds = 8;
 constexpr int kXcdRun = 32;                           // consecutive logical tiles kept on one XCD
+#ifndef DMA_N3
+#define DMA_N3 8
+#endif
+#ifndef DMA_N0
+#define DMA_N0 8
+#endif
+constexpr int kLoadsStep3 = DMA_N3;                   // of the 16 loads of a stage fill: issued in step 3,
+constexpr int kLoadsStep0 = DMA_N0;                   // in step 0 of the next turn (the rest in step 1)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -42,11 +54,11 @@ typedef __attribute__((address_space(3))) bf16x4* LdsBf16x4Ptr;
 #define TF_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define TF_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
+// two binary32 -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a = ((a & 0x7fffffffu) > 0x7f800000u) ? ((a >> 16) | 0x40u) : ((a + 0x7fffu + ((a >> 16) & 1u)) >> 16);
-    b = ((b & 0x7fffffffu) > 0x7f800000u) ? ((b >> 16) | 0x40u) : ((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
-    return (a & 0xffffu) | (b << 16);
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
 }
 
 // blockIdx -> logical tile.  Hardware hands workgroup b to XCD b % 8; runs of kXcdRun
@@ -69,9 +81,11 @@ __device__ __forceinline__ int logical_tile(int b, int nb) {
 //        logical 64-byte block = physical block ^ (T & 3).
 // ---------------------------------------------------------------------------------------------
 struct FillPtrs {
-    const char* a[2];         // per-lane global byte pointers of load p = 0 (and p = 1 for kNT)
-    const char* b[2];
-    int64_t step_a, step_b;   // byte distance between loads p and p + 2 (kNT) / p and p + 1 (kTN)
+    const char* base_a;       // wave-uniform global byte address of the tile's first element
+    const char* base_b;
+    int64_t pstep_a, pstep_b; // wave-uniform byte distance between loads p and p + 1
+    uint32_t voff_a[2];       // per-lane byte offsets (even / odd p for kNT, identical for kTN)
+    uint32_t voff_b[2];
 };
 
 template <bool kTN>
@@ -84,58 +98,60 @@ __device__ __forceinline__ FillPtrs make_fill(const uint16_t* A, const uint16_t*
         const int slot = lane & 31;
         const int blk = (slot >> 2) ^ (T & 3);
         const int col = blk * 32 + (slot & 3) * 8;             // element offset inside the 256-wide tile row
-        f.a[0] = reinterpret_cast<const char*>(A + int64_t(T) * lda + m0 + col);
-        f.b[0] = reinterpret_cast<const char*>(B + int64_t(T) * ldb + n0 + col);
-        f.a[1] = f.a[0]; f.b[1] = f.b[0];
-        f.step_a = 8 * lda * 2; f.step_b = 8 * ldb * 2;
+        f.base_a = reinterpret_cast<const char*>(A + m0);
+        f.base_b = reinterpret_cast<const char*>(B + n0);
+        f.voff_a[0] = f.voff_a[1] = uint32_t((int64_t(T) * lda + col) * 2);
+        f.voff_b[0] = f.voff_b[1] = uint32_t((int64_t(T) * ldb + col) * 2);
+        f.pstep_a = 8 * lda * 2; f.pstep_b = 8 * ldb * 2;
     } else {
         const int r = 8 * w + (lane >> 3);                     // + 32 p
         const int pc = lane & 7;
+        f.base_a = reinterpret_cast<const char*>(A + int64_t(m0) * lda);
+        f.base_b = reinterpret_cast<const char*>(B + int64_t(n0) * ldb);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {                          // p even / odd differ in bit 2 of the swizzle
             const int R = r + 32 * q;
             const int c = pc ^ ((R ^ (R >> 3)) & 7);
-            f.a[q] = reinterpret_cast<const char*>(A + int64_t(m0 + R) * lda + c * 8);
-            f.b[q] = reinterpret_cast<const char*>(B + int64_t(n0 + R) * ldb + c * 8);
+            f.voff_a[q] = uint32_t((int64_t(r) * lda + c * 8) * 2);
+            f.voff_b[q] = uint32_t((int64_t(r) * ldb + c * 8) * 2);
         }
-        f.step_a = 64 * lda * 2; f.step_b = 64 * ldb * 2;
+        f.pstep_a = 32 * lda * 2; f.pstep_b = 32 * ldb * 2;
     }
     return f;
 }
 
-// One direct-to-LDS load: every lane fetches 16 bytes from its own global address and the
-// wave's 1 KB lands at LDS byte address lds_base (wave-uniform, goes through M0) + 16 * lane.
+// One direct-to-LDS load: lane i fetches 16 bytes from gbase + voff and the wave's 1 KB lands
+// at LDS byte address lds_wave_base + kLdsOff + 16 i (the LDS address goes through M0).
 // Written as inline assembly so that the compiler's wait-count insertion does not treat every
 // later LDS read as dependent on it (it would drain the load queue before each transpose read);
 // completion is awaited explicitly with wait_direct_loads() before the stage barrier.
-__device__ __forceinline__ void direct_load_16B(const char* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+template <int kLdsOff>
+__device__ __forceinline__ void direct_load_16B(const char* gbase, uint32_t voff, uint32_t lds_wave_base) {
+    asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
                  :
-                 : "s"(lds_base), "v"(gptr)
+                 : "s"(lds_wave_base), "n"(kLdsOff), "v"(voff), "s"(gbase)
                  : "memory");
 }
 __device__ __forceinline__ void wait_direct_loads() {
     __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0), other counters untouched
 }
 
-// Issue load number q (0..15) of a stage fill: even q fetch operand A, odd q operand B, load p = q / 2.
-template <bool kTN>
-__device__ __forceinline__ void fill_one(const FillPtrs& f, int64_t koff_a, int64_t koff_b, uint32_t stage_lds, int q) {
-    const uint32_t w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int p = q >> 1;
-    if ((q & 1) == 0) {
-        const char* ga = kTN ? f.a[0] + koff_a + p * f.step_a : f.a[p & 1] + koff_a + (p >> 1) * f.step_a;
-        direct_load_16B(ga, stage_lds + w * 1024 + p * 4096);
-    } else {
-        const char* gb = kTN ? f.b[0] + koff_b + p * f.step_b : f.b[p & 1] + koff_b + (p >> 1) * f.step_b;
-        direct_load_16B(gb, stage_lds + kTileBytes + w * 1024 + p * 4096);
-    }
+// Issue load number q (0..15) of a stage fill: even q fetch operand A, odd q operand B, load
+// p = q / 2.  ka / kb are the wave-uniform byte offsets of the contraction step to fetch;
+// lds_wave_base is the LDS byte address of the stage plus 1 KB times the wave index.
+template <bool kTN, int q>
+__device__ __forceinline__ void fill_one(const FillPtrs& f, int64_t ka, int64_t kb, uint32_t lds_wave_base) {
+    constexpr int p = q >> 1;
+    if ((q & 1) == 0) direct_load_16B<p * 4096>(f.base_a + ka + p * f.pstep_a, f.voff_a[p & 1], lds_wave_base);
+    else direct_load_16B<kTileBytes + p * 4096>(f.base_b + kb + p * f.pstep_b, f.voff_b[p & 1], lds_wave_base);
 }
 
-template <bool kTN>
-__device__ __forceinline__ void fill_stage(const FillPtrs& f, int64_t koff_a, int64_t koff_b, uint32_t stage) {
-#pragma unroll
-    for (int q = 0; q < 16; ++q) fill_one<kTN>(f, koff_a, koff_b, stage, q);
+template <bool kTN, int q = 0, int end = 16>
+__device__ __forceinline__ void fill_stage(const FillPtrs& f, int64_t ka, int64_t kb, uint32_t lds_wave_base) {
+    if constexpr (q < end) {
+        fill_one<kTN, q>(f, ka, kb, lds_wave_base);
+        fill_stage<kTN, q + 1, end>(f, ka, kb, lds_wave_base);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -230,51 +246,118 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     const FragAddr fr = make_frag_addr<kTN>(wm, wn);
     const int nk = Kc / kBK;
 
-    // LDS byte address of the dynamic shared array (a 32-bit LDS pointer is its byte offset)
-    const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
-        uint32_t(reinterpret_cast<uintptr_t>(TF_LPTR(lds))));
-    fill_stage<kTN>(fp, 0, 0, lds_base);
-    wait_direct_loads();
-    __syncthreads();                      // this wave's loads have landed, now everyone else's too
+    // LDS byte address of the dynamic shared array (a 32-bit LDS pointer is its byte offset),
+    // plus this wave's 1 KB slot inside every 4 KB group of a stage fill.
+    const uint32_t lds_wave_base = __builtin_amdgcn_readfirstlane(
+        uint32_t(reinterpret_cast<uintptr_t>(TF_LPTR(lds))) + uint32_t(wave) * 1024u);
 
+    // prologue: stage 0 <- step 0, stage 1 <- step 1 (step 0 again if there is only one)
+    fill_stage<kTN>(fp, 0, 0, lds_wave_base);
+    wait_direct_loads();
+    __syncthreads();
+    {
+        const int k1 = min(1, nk - 1);     // first part of stage 1; the loop issues the rest
+        fill_stage<kTN, 0, kLoadsStep3>(fp, k1 * kstep_a, k1 * kstep_b, lds_wave_base + kStageBytes);
+    }
+    bf16x8 fa[2][4], fb[2][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        fa[0][i] = load_frag<kTN>(lds, fr.a[i], 0);
+        fb[0][i] = load_frag<kTN>(lds, fr.b[i], 0);
+    }
+
+#ifdef EXP_STAMP
+    long long stamp_acc[6] = {0, 0, 0, 0, 0, 0};
+#endif
     for (int kt = 0; kt < nk; ++kt) {
         const char* cur = lds + (kt & 1) * kStageBytes;
-        const uint32_t nxt = lds_base + ((kt + 1) & 1) * kStageBytes;
-        // The last step has nothing left to fetch; it re-fetches its own tile into the stage
-        // nobody reads any more, which keeps the loop body one straight-line block.
-        const int kn = min(kt + 1, nk - 1);
-        const int64_t koff_a = kn * kstep_a, koff_b = kn * kstep_b;
+        const char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
+        const uint32_t cur_fill = lds_wave_base + (kt & 1) * kStageBytes;
+        // Contraction step fetched into `cur` once everybody is done reading it; past the end
+        // the last step is fetched again (into a stage nobody reads any more), which keeps the
+        // loop body free of branches.
+        const int kf = min(kt + 2, nk - 1), kf1 = min(kt + 1, nk - 1);
+        const int64_t ka = kf * kstep_a, kb = kf * kstep_b;          // fetched during step 3, into `cur`
+        const int64_t ka1 = kf1 * kstep_a, kb1 = kf1 * kstep_b;      // rest of the previous fill, into `nxt`
+        const uint32_t nxt_fill = lds_wave_base + ((kt + 1) & 1) * kStageBytes;
 
-        // Issue order is pinned with scheduling fences: operands of step 0, then every MFMA of
-        // step s is followed by one operand read of step s + 1 and, in step 0, by one
-        // direct-to-LDS load of the next stage, so LDS and memory latency hide behind the
-        // matrix cores.
-        bf16x8 fa[2][4], fb[2][4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            fa[0][i] = load_frag<kTN>(cur, fr.a[i], 0);
-            fb[0][i] = load_frag<kTN>(cur, fr.b[i], 0);
-        }
+        // Issue order below is pinned with scheduling fences.
         __builtin_amdgcn_sched_barrier(0);
+#ifdef EXP_STAMP
+        long long t_prev = clock64();
+        __builtin_amdgcn_sched_barrier(0);
+#define STAMP(k) { __builtin_amdgcn_sched_barrier(0); long long t_now = clock64(); stamp_acc[k] += t_now - t_prev; t_prev = t_now; __builtin_amdgcn_sched_barrier(0); }
+#else
+#define STAMP(k) {}
+#endif
 #pragma unroll
-        for (int s = 0; s < kBK / 16; ++s) {
+        for (int s = 0; s < 4; ++s) {
+            if (s == 3) {
+                // every operand read of this stage has been issued: wait for them and for this
+                // wave's part of the next stage, then meet the other waves.  After the barrier
+                // the next stage is complete and this one may be overwritten.
+                STAMP(2)
+                wait_direct_loads();
+                STAMP(3)
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+                STAMP(4)
+            }
+            if (s == 1) { STAMP(0) }
+            if (s == 2) { STAMP(1) }
+            const char* rd = s == 3 ? nxt : cur;     // step 3 reads step 0 of the next stage
+            const int rs = s == 3 ? 0 : s + 1;
 #pragma unroll
             for (int q = 0; q < 16; ++q) {
                 const int i = q >> 2, j = q & 3;
                 // D rows <- n (B operand rows), D columns <- m: a lane then owns 4 consecutive n
                 // of one output row m, i.e. 4 contiguous elements of row-major C.
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s & 1][j], fa[s & 1][i], acc[i][j], 0, 0, 0);
-                if (s + 1 < kBK / 16 && q < 8) {
-                    if (q & 1) fb[(s + 1) & 1][q >> 1] = load_frag<kTN>(cur, fr.b[q >> 1], s + 1);
-                    else       fa[(s + 1) & 1][q >> 1] = load_frag<kTN>(cur, fr.a[q >> 1], s + 1);
+                if (q < 8) {
+                    if (q & 1) fb[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.b[q >> 1], rs);
+                    else       fa[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.a[q >> 1], rs);
                 }
-                if (s == 0) fill_one<kTN>(fp, koff_a, koff_b, nxt, q);
+#ifndef EXP_NO_DMA
+                {
+                    // Which direct-to-LDS load (0..15, -1 = none) follows MFMA q of step s.  The
+                    // loads of one stage fill are spread over step 3 (right after the barrier that
+                    // frees the stage) and steps 0..1 of the next stage's turn, so that the
+                    // texture-address unit, which all four waves share, is never asked for more
+                    // than it can take while the matrix cores run.
+                    constexpr int n3 = kLoadsStep3, n0 = kLoadsStep0, n1 = 16 - n3 - n0;
+                    const int cnt = s == 3 ? n3 : s == 0 ? n0 : s == 1 ? n1 : 0;
+                    const int first = s == 3 ? 0 : s == 0 ? n3 : n3 + n0;
+                    int load = -1;
+                    if (cnt > 0) {
+                        const int stride = 16 / cnt;
+                        if (q % stride == 0 && q / stride < cnt) load = first + q / stride;
+                    }
+                    const int64_t la = s == 3 ? ka : ka1, lb = s == 3 ? kb : kb1;
+                    const uint32_t dst = s == 3 ? cur_fill : nxt_fill;
+                    switch (load) {
+#define TF_FILL_CASE(Q) case Q: fill_one<kTN, Q>(fp, la, lb, dst); break;
+                        TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
+                        TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
+                        TF_FILL_CASE(8) TF_FILL_CASE(9) TF_FILL_CASE(10) TF_FILL_CASE(11)
+                        TF_FILL_CASE(12) TF_FILL_CASE(13) TF_FILL_CASE(14) TF_FILL_CASE(15)
+#undef TF_FILL_CASE
+                        default: break;
+                    }
+                }
+#endif
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if (s == 3) { STAMP(5) }
         }
-        wait_direct_loads();
-        __syncthreads();                  // next stage landed everywhere, this one is free to overwrite
     }
+    wait_direct_loads();      // nothing of this workgroup may still be in flight towards LDS
+#ifdef EXP_STAMP
+    if (blockIdx.x == 300 && threadIdx.x == 0) {
+        long long* dbg = reinterpret_cast<long long*>(const_cast<void*>(batch.p[63].A));
+        for (int k = 0; k < 6; ++k) dbg[k] = stamp_acc[k];
+        dbg[6] = nk;
+    }
+#endif
 
     // epilogue: acc[i][j][4g + e] is C[m][n] with m = m0 + wm*128 + i*32 + lane%32,
     // n = n0 + wn*128 + j*32 + 8g + 4*(lane/32) + e.
