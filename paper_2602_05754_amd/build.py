@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 
@@ -14,6 +15,7 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
     "-Wall", "-Wno-unused-command-line-argument",
+    "-Rpass-analysis=kernel-resource-usage",      # per-kernel register / scratch report, checked below
 ]
 
 
@@ -25,10 +27,24 @@ def build(verbose: bool = False) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in res.stderr.splitlines() if noise not in l)
+    remarks = [l for l in err.splitlines() if "-Rpass-analysis=kernel-resource-usage" in l]
+    err = "\n".join(l for l in err.splitlines() if "-Rpass-analysis=kernel-resource-usage" not in l)
+    if remarks:   # source-context lines that clang prints under every remark
+        err = "\n".join(l for l in err.splitlines() if not re.match(r"^\s*(\d+\s*)?\|", l))
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err, file=sys.stderr)
+    # The staged registers of the GEMM kernels must stay in registers: a kernel that uses
+    # scratch memory has lost an order of magnitude of speed, so treat it as a build error.
+    name = None
+    for l in remarks:
+        m = re.search(r"Function Name: (\S+)", l)
+        if m:
+            name = m.group(1)
+        m = re.search(r"ScratchSize \[bytes/lane\]: (\d+)", l)
+        if m and int(m.group(1)) != 0:
+            raise RuntimeError(f"kernel {name} uses {m.group(1)} bytes/lane of scratch memory")
     return LIB
 
 

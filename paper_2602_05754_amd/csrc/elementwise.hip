@@ -6,21 +6,21 @@
 //
 // HBM-bound: per unfrozen element 22 B are read (p, m, v, E, A fp32 + bf16
 // grad) and 22 B written (p, m, v, E, A + bf16 copy of p).  Each thread owns
-// groups of 8 consecutive elements so that every access is a 16-byte vector
-// (two for fp32 arrays); a frozen element is written back with the very bits
-// that were read, a fully frozen group is neither read nor written.
+// groups of 4 consecutive elements, so a wave's access to an fp32 array is one
+// contiguous KB of 16-byte vectors; a frozen element is written back with the
+// very bits that were read, a fully frozen group is neither read nor written.
 #include "tf_internal.h"
 
 namespace tf {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kGroup = 8;          // elements per thread per iteration
-constexpr int kIters = 2;          // iterations per block
+constexpr int kGroup = 4;          // consecutive elements per thread per iteration (one 16-byte fp32 vector)
+constexpr int kIters = 4;          // iterations per block
 constexpr int64_t kElemsPerBlock = int64_t(kThreads) * kGroup * kIters;
 
-struct alignas(16) F4 { float x, y, z, w; };
-struct alignas(16) U4 { uint32_t x, y, z, w; };
+typedef float F4 __attribute__((ext_vector_type(4)));
+typedef uint32_t U2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
@@ -31,16 +31,13 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
-__device__ __forceinline__ void load8(const float* ptr, float (&out)[8]) {
+__device__ __forceinline__ void load4(const float* ptr, float (&out)[4]) {
     const F4 a = *reinterpret_cast<const F4*>(ptr);
-    const F4 b = *reinterpret_cast<const F4*>(ptr + 4);
     out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
-    out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
 }
 
-__device__ __forceinline__ void store8(float* ptr, const float (&in)[8]) {
+__device__ __forceinline__ void store4(float* ptr, const float (&in)[4]) {
     *reinterpret_cast<F4*>(ptr) = F4{in[0], in[1], in[2], in[3]};
-    *reinterpret_cast<F4*>(ptr + 4) = F4{in[4], in[5], in[6], in[7]};
 }
 
 // One element of the AdamW step; returns the applied update u = p_new - p_old.
@@ -90,49 +87,45 @@ __global__ __launch_bounds__(kThreads) void ew_kernel(EwBatch batch, AdamwParams
         const int64_t e0 = chunk + (int64_t(it) * kThreads + threadIdx.x) * kGroup;
         if (e0 >= numel) continue;
         if (e0 + kGroup <= numel) {
-            // ---------------- vector path: 8 elements ----------------
-            const uint32_t fz = mask_bytes ? uint32_t(mask_bytes[e0 >> 3]) : 0u;
-            if (fz == 0xffu) {
+            // ---------------- vector path: 4 elements, a wave touches 1 KB of each fp32 array ----------------
+            const uint32_t fz = mask_bytes ? (uint32_t(mask_bytes[e0 >> 3]) >> (e0 & 4)) & 0xfu : 0u;
+            if (fz == 0xfu) {
                 if (want_sums) {
-                    float E[8], A[8];
-                    load8(T.E + e0, E);
-                    load8(T.A + e0, A);
-                    float se = 0.f, sa = 0.f;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) { se += fabsf(E[j]); sa += A[j]; }
-                    sum_e += double(se); sum_a += double(sa);
+                    float E[4], A[4];
+                    load4(T.E + e0, E);
+                    load4(T.A + e0, A);
+                    sum_e += double(fabsf(E[0]) + fabsf(E[1]) + fabsf(E[2]) + fabsf(E[3]));
+                    sum_a += double(A[0] + A[1] + A[2] + A[3]);
                 }
                 continue;
             }
-            float p[8], m[8], v[8], g[8], E[8], A[8];
+            float p[4], m[4], v[4], g[4], E[4], A[4];
             if (kAdamw) {
-                load8(T.p + e0, p);
-                load8(T.m + e0, m);
-                load8(T.v + e0, v);
+                load4(T.p + e0, p);
+                load4(T.m + e0, m);
+                load4(T.v + e0, v);
                 if (kGradBf16) {
-                    const U4 q = *reinterpret_cast<const U4*>(static_cast<const uint16_t*>(T.g) + e0);
+                    const U2 q = *reinterpret_cast<const U2*>(static_cast<const uint16_t*>(T.g) + e0);
                     g[0] = bf16_bits_to_f32(q.x & 0xffffu); g[1] = bf16_bits_to_f32(q.x >> 16);
                     g[2] = bf16_bits_to_f32(q.y & 0xffffu); g[3] = bf16_bits_to_f32(q.y >> 16);
-                    g[4] = bf16_bits_to_f32(q.z & 0xffffu); g[5] = bf16_bits_to_f32(q.z >> 16);
-                    g[6] = bf16_bits_to_f32(q.w & 0xffffu); g[7] = bf16_bits_to_f32(q.w >> 16);
                 } else {
-                    load8(static_cast<const float*>(T.g) + e0, g);
+                    load4(static_cast<const float*>(T.g) + e0, g);
                 }
             } else {
-                load8(static_cast<const float*>(T.g) + e0, g);
+                load4(static_cast<const float*>(T.g) + e0, g);
             }
             if (has_ema) {
-                load8(T.E + e0, E);
-                load8(T.A + e0, A);
+                load4(T.E + e0, E);
+                load4(T.A + e0, A);
             }
-            U4 low_old = U4{0, 0, 0, 0};
+            U2 low_old = {0, 0};
             const bool has_low = kAdamw && T.p_lowp != nullptr;
-            if (has_low && fz != 0u) low_old = *reinterpret_cast<const U4*>(T.p_lowp + e0);
+            if (has_low && fz != 0u) low_old = *reinterpret_cast<const U2*>(T.p_lowp + e0);
 
-            uint32_t low[8];
+            uint32_t low[4];
             float se = 0.f, sa = 0.f;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
+            for (int j = 0; j < 4; ++j) {
                 const bool frozen = (fz >> j) & 1u;
                 float pn = 0.f, mn = 0.f, vn = 0.f, En = 0.f, An = 0.f;
                 if (kAdamw) {
@@ -153,34 +146,29 @@ __global__ __launch_bounds__(kThreads) void ew_kernel(EwBatch batch, AdamwParams
                 }
             }
             if (kAdamw) {
-                store8(T.p + e0, p);
-                store8(T.m + e0, m);
-                store8(T.v + e0, v);
+                store4(T.p + e0, p);
+                store4(T.m + e0, m);
+                store4(T.v + e0, v);
                 if (has_low) {
-                    U4 o;
+                    U2 o;
                     o.x = low[0] | (low[1] << 16); o.y = low[2] | (low[3] << 16);
-                    o.z = low[4] | (low[5] << 16); o.w = low[6] | (low[7] << 16);
                     if (fz != 0u) {
                         // keep the stored bf16 of frozen elements
                         const uint32_t k0 = ((fz & 1u) ? 0xffffu : 0u) | ((fz & 2u) ? 0xffff0000u : 0u);
                         const uint32_t k1 = ((fz & 4u) ? 0xffffu : 0u) | ((fz & 8u) ? 0xffff0000u : 0u);
-                        const uint32_t k2 = ((fz & 16u) ? 0xffffu : 0u) | ((fz & 32u) ? 0xffff0000u : 0u);
-                        const uint32_t k3 = ((fz & 64u) ? 0xffffu : 0u) | ((fz & 128u) ? 0xffff0000u : 0u);
                         o.x = (o.x & ~k0) | (low_old.x & k0);
                         o.y = (o.y & ~k1) | (low_old.y & k1);
-                        o.z = (o.z & ~k2) | (low_old.z & k2);
-                        o.w = (o.w & ~k3) | (low_old.w & k3);
                     }
-                    *reinterpret_cast<U4*>(T.p_lowp + e0) = o;
+                    *reinterpret_cast<U2*>(T.p_lowp + e0) = o;
                 }
             }
             if (has_ema) {
-                store8(T.E + e0, E);
-                store8(T.A + e0, A);
+                store4(T.E + e0, E);
+                store4(T.A + e0, A);
                 sum_e += double(se); sum_a += double(sa);
             }
         } else {
-            // ---------------- ragged tail: < 8 elements, one at a time ----------------
+            // ---------------- ragged tail: < 4 elements, one at a time ----------------
             for (int64_t e = e0; e < numel; ++e) {
                 const bool frozen = T.bits && ((T.bits[e >> 5] >> (e & 31)) & 1u);
                 if (frozen) {

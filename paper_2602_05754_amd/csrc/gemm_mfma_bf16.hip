@@ -35,14 +35,8 @@ constexpr int kLdsBytes = 2 * kStageBytes;            // two stages = 128 KB
 constexpr int kGroupM = 8;                            // tile rows per L2 locality group
 constexpr int kXcds = 8;
 constexpr int kXcdRun = 32;                           // consecutive logical tiles kept on one XCD
-#ifndef DMA_N3
-#define DMA_N3 8
-#endif
-#ifndef DMA_N0
-#define DMA_N0 8
-#endif
-constexpr int kLoadsStep3 = DMA_N3;                   // of the 16 loads of a stage fill: issued in step 3,
-constexpr int kLoadsStep0 = DMA_N0;                   // in step 0 of the next turn (the rest in step 1)
+constexpr int kLoadsStep3 = 8;                        // of the 16 loads of a stage fill: issued in step 3,
+constexpr int kLoadsStep0 = 8;                        // in step 0 of the next turn (the rest in step 1)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -266,9 +260,6 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
         fb[0][i] = load_frag<kTN>(lds, fr.b[i], 0);
     }
 
-#ifdef EXP_STAMP
-    long long stamp_acc[6] = {0, 0, 0, 0, 0, 0};
-#endif
     for (int kt = 0; kt < nk; ++kt) {
         const char* cur = lds + (kt & 1) * kStageBytes;
         const char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
@@ -283,28 +274,16 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
 
         // Issue order below is pinned with scheduling fences.
         __builtin_amdgcn_sched_barrier(0);
-#ifdef EXP_STAMP
-        long long t_prev = clock64();
-        __builtin_amdgcn_sched_barrier(0);
-#define STAMP(k) { __builtin_amdgcn_sched_barrier(0); long long t_now = clock64(); stamp_acc[k] += t_now - t_prev; t_prev = t_now; __builtin_amdgcn_sched_barrier(0); }
-#else
-#define STAMP(k) {}
-#endif
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             if (s == 3) {
                 // every operand read of this stage has been issued: wait for them and for this
                 // wave's part of the next stage, then meet the other waves.  After the barrier
                 // the next stage is complete and this one may be overwritten.
-                STAMP(2)
                 wait_direct_loads();
-                STAMP(3)
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
-                STAMP(4)
             }
-            if (s == 1) { STAMP(0) }
-            if (s == 2) { STAMP(1) }
             const char* rd = s == 3 ? nxt : cur;     // step 3 reads step 0 of the next stage
             const int rs = s == 3 ? 0 : s + 1;
 #pragma unroll
@@ -317,7 +296,6 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
                     if (q & 1) fb[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.b[q >> 1], rs);
                     else       fa[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.a[q >> 1], rs);
                 }
-#ifndef EXP_NO_DMA
                 {
                     // Which direct-to-LDS load (0..15, -1 = none) follows MFMA q of step s.  The
                     // loads of one stage fill are spread over step 3 (right after the barrier that
@@ -344,20 +322,11 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
                         default: break;
                     }
                 }
-#endif
                 __builtin_amdgcn_sched_barrier(0);
             }
-            if (s == 3) { STAMP(5) }
         }
     }
     wait_direct_loads();      // nothing of this workgroup may still be in flight towards LDS
-#ifdef EXP_STAMP
-    if (blockIdx.x == 300 && threadIdx.x == 0) {
-        long long* dbg = reinterpret_cast<long long*>(const_cast<void*>(batch.p[63].A));
-        for (int k = 0; k < 6; ++k) dbg[k] = stamp_acc[k];
-        dbg[6] = nk;
-    }
-#endif
 
     // epilogue: acc[i][j][4g + e] is C[m][n] with m = m0 + wm*128 + i*32 + lane%32,
     // n = n0 + wn*128 + j*32 + 8g + 4*(lane/32) + e.
