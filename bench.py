@@ -49,6 +49,9 @@ def parse():
     ap.add_argument("--workload", type=int, default=2, choices=[2, 3], help="config id (2 = LLaMA-1B-shaped stage)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device copy a few times (reference for the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     return ap.parse_args()
 
 
@@ -119,7 +122,7 @@ def cpu_baseline(cfg, wl, r):
     """Time the fp64 oracle on a bounded sample of the same workload: block 0's
     seven layers, the first Ts tokens, backward at ratio r + AdamW/EMA step."""
     import oracle
-    Ts = 512
+    Ts = 2048
     sub = wl.scaled(cfg, blocks=1)
     sh = sub.shapes
     mask = wl.permutation_mask(sub, r)
@@ -167,8 +170,21 @@ def main():
         sys.exit(2)
     if not os.path.exists(tf.library_path()):
         raise RuntimeError("libtf.so has not been built (python -c 'import __graft_entry__ as g; g.build()')")
-    cfg = wl.CONFIGS[args.workload]
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = 1 << 30
+        a = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 5
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n,
+                          "GBps": 2 * n / dt / 1e9}), flush=True)
+        return
+    cfg = wl.CONFIGS[args.workload]
     ctx = tf.Context(0)
     st = Stage(cfg, wl, tf, torch)
     L, T, P = st.L, st.T, cfg.n_params

@@ -42,6 +42,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t U2 __attribute__((ext_vector_type(2)));
+typedef uint32_t U4 __attribute__((ext_vector_type(4)));
 typedef float F4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) bf16x4* LdsBf16x4Ptr;
 
@@ -329,31 +330,59 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     wait_direct_loads();      // nothing of this workgroup may still be in flight towards LDS
 
     // epilogue: acc[i][j][4g + e] is C[m][n] with m = m0 + wm*128 + i*32 + lane%32,
-    // n = n0 + wn*128 + j*32 + 8g + 4*(lane/32) + e.
+    // n = n0 + wn*128 + j*32 + 8g + 4*(lane/32) + e.  A lane's values are scattered over the
+    // tile, so each wave first turns its 128 x 128 block around in its own 32 KB quarter of the
+    // (now idle) LDS and then writes whole rows: 16 lanes x 16 bytes cover 256 contiguous bytes.
+    __syncthreads();                                   // every wave is done reading the stages
+    char* wlds = lds + wave * 32768;
     const int lrow = lane & 31, lhalf = lane >> 5;
+    if (kOutBf16) {
+        // [128 rows][32 chunks of 8 bytes], chunk index XORed with the row to spread the banks
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int64_t m = m0 + wm * 128 + i * 32 + lrow;
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * 128 + j * 32 + 8 * g + 4 * lhalf;
-                const int64_t off = m * N + n;
-                const float c0 = acc[i][j][4 * g + 0], c1 = acc[i][j][4 * g + 1];
-                const float c2 = acc[i][j][4 * g + 2], c3 = acc[i][j][4 * g + 3];
-                if (kOutBf16) {
-                    *reinterpret_cast<U2*>(static_cast<uint16_t*>(P.C) + off) =
-                        U2{f32x2_to_bf16x2(c0, c1), f32x2_to_bf16x2(c2, c3)};
-                } else {
-                    F4* dst = reinterpret_cast<F4*>(static_cast<float*>(P.C) + off);
-                    if (kAccumulate) {
-                        const F4 old = *dst;
-                        *dst = F4{old.x + c0, old.y + c1, old.z + c2, old.w + c3};
-                    } else {
-                        *dst = F4{c0, c1, c2, c3};
-                    }
+                for (int g = 0; g < 4; ++g) {
+                    const int m = i * 32 + lrow, c = 8 * j + 2 * g + lhalf;
+                    *reinterpret_cast<U2*>(wlds + m * 256 + ((c ^ lrow) << 3)) =
+                        U2{f32x2_to_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]),
+                           f32x2_to_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3])};
                 }
+        const int cb = lane & 15, rsub = lane >> 4;    // 16-byte column block, row inside a group of 4
+        uint16_t* Cw = static_cast<uint16_t*>(P.C) + int64_t(m0 + wm * 128) * N + n0 + wn * 128 + cb * 8;
+#pragma unroll 8
+        for (int it = 0; it < 32; ++it) {
+            const int m = it * 4 + rsub, x = m & 31;
+            // chunks 2cb and 2cb+1 sit in one aligned 16-byte pair, swapped when the row is odd
+            U4 v = *reinterpret_cast<const U4*>(wlds + m * 256 + (((2 * cb) ^ (x & 30)) << 3));
+            if (x & 1) v = U4{v.z, v.w, v.x, v.y};
+            *reinterpret_cast<U4*>(Cw + int64_t(m) * N) = v;
+        }
+    } else {
+        // fp32: two passes of 64 rows, [64 rows][32 chunks of 16 bytes]
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+            for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const int i = 2 * h + ii;
+                        const int m = ii * 32 + lrow, c = 8 * j + 2 * g + lhalf;
+                        *reinterpret_cast<F4*>(wlds + m * 512 + ((c ^ lrow) << 4)) =
+                            F4{acc[i][j][4 * g + 0], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                    }
+            const int cb = lane & 31, rsub = lane >> 5;    // 16-byte column block, row inside a pair
+            float* Cw = static_cast<float*>(P.C) + int64_t(m0 + wm * 128 + h * 64) * N + n0 + wn * 128 + cb * 4;
+#pragma unroll 8
+            for (int it = 0; it < 32; ++it) {
+                const int m = it * 2 + rsub;
+                F4 v = *reinterpret_cast<const F4*>(wlds + m * 512 + ((cb ^ (m & 31)) << 4));
+                F4* dst = reinterpret_cast<F4*>(Cw + int64_t(m) * N);
+                if (kAccumulate) v += *dst;
+                *dst = v;
             }
         }
     }
