@@ -18,6 +18,7 @@ One JSON line is printed on stdout; progress goes to stderr.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -210,11 +211,14 @@ def main():
         torch.cuda.synchronize()
         ctx.profile_enable(True)
         ctx.profile_collect()
+        gc.collect()
+        gc.disable()            # a generational collection of the interpreter costs tens of ms
         t0 = time.perf_counter()
         for _ in range(steps):
             st.step(ctx, mask, n)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
+        gc.enable()
         prof = ctx.profile_collect()
         ctx.profile_enable(False)
         per_kind = {}
