@@ -5,15 +5,17 @@
 // Only tensors that are not frozen are ever listed in a kTN batch, so a frozen
 // tensor's dW tiles cost nothing and its buffers are never touched.
 //
-// One 256 x 256 output tile per 256-thread workgroup (4 wave64s in a 2 x 2
-// grid, 128 x 128 per wave = 4 x 4 MFMA 32x32x16 tiles, 256 fp32 accumulators
-// per lane).  The contraction advances 64 at a time through two LDS stages of
-// 64 KB that are filled by direct global->LDS loads (no register staging):
-// while the matrix cores work on one stage the next one is in flight.  A stage
-// is consumed in four steps of 16; the operands of step s + 1 are read from LDS
-// while the MFMAs of step s issue, the stage barrier sits after the reads of the
-// last step, and the first operands of the next stage are read during the last
-// step, so neither LDS latency nor the barrier leaves the matrix cores idle.
+// One 256 x 256 output tile per workgroup.  The waves form a 2 x kWN grid
+// (kWN = 2: 4 waves of 128 x 128, 256 accumulators per lane; kWN = 4: 8 waves of
+// 128 x 64, 128 accumulators per lane, two waves per SIMD), each wave owning
+// 4 x (8 / kWN) MFMA 32x32x16 tiles.  The contraction advances 64 at a time
+// through two LDS stages of 64 KB that are filled by direct global->LDS loads
+// (no register staging): while the matrix cores work on one stage the next one
+// is in flight.  A stage is consumed in four steps of 16; the operands of step
+// s + 1 are read from LDS while the MFMAs of step s issue, the stage barrier
+// sits after the reads of the last step, and the first operands of the next
+// stage are read during the last step, so neither LDS latency nor the barrier
+// leaves the matrix cores idle.
 //
 //   kNT stage: [256 rows][64 contraction] per operand, 16-byte chunks of a row
 //              XOR-swizzled; MFMA operands are plain 128-bit LDS reads.
@@ -28,15 +30,30 @@ namespace tf {
 namespace {
 
 constexpr int kBM = 256, kBN = 256, kBK = 64;
-constexpr int kThreads = 256;
 constexpr int kTileBytes = kBM * kBK * 2;             // 32 KB per operand per stage
 constexpr int kStageBytes = 2 * kTileBytes;           // A + B
 constexpr int kLdsBytes = 2 * kStageBytes;            // two stages = 128 KB
 constexpr int kGroupM = 8;                            // tile rows per L2 locality group
 constexpr int kXcds = 8;
 constexpr int kXcdRun = 32;                           // consecutive logical tiles kept on one XCD
-constexpr int kLoadsStep3 = 8;                        // of the 16 loads of a stage fill: issued in step 3,
-constexpr int kLoadsStep0 = 8;                        // in step 0 of the next turn (the rest in step 1)
+
+#ifndef TF_GEMM_WN
+#define TF_GEMM_WN 2
+#endif
+
+template <int kWN>
+struct Shape {
+    static constexpr int kWaves = 2 * kWN;                  // 4 or 8
+    static constexpr int kThreads = 64 * kWaves;
+    static constexpr int kWaveN = kBN / kWN;                // columns per wave: 128 or 64
+    static constexpr int kNJ = kWaveN / 32;                 // MFMA column blocks per wave: 4 or 2
+    static constexpr int kMfmaPerStep = 4 * kNJ;            // 16 or 8
+    static constexpr int kReadsPerStep = 4 + kNJ;           // operand fragments per step: 8 or 6
+    static constexpr int kLoadsPerOperand = 32 / kWaves;    // 1 KB loads per wave, operand and stage: 8 or 4
+    static constexpr int kLoads = 2 * kLoadsPerOperand;     // 16 or 8
+    static constexpr int kLoadsStep3 = kLoads / 2;          // issued in step 3; the rest in the next step 0
+    static constexpr int kEpiBytes = kLdsBytes / kWaves;    // LDS per wave for the epilogue: 32 or 16 KB
+};
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -46,7 +63,6 @@ typedef uint32_t U4 __attribute__((ext_vector_type(4)));
 typedef float F4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) bf16x4* LdsBf16x4Ptr;
 
-#define TF_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
 #define TF_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
 
 // two binary32 -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32)
@@ -68,28 +84,28 @@ __device__ __forceinline__ int logical_tile(int b, int nb) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Stage fill.  Each wave issues 8 direct-to-LDS loads per operand; load p of wave w fills the
-// 1 KB of the operand tile at (4 p + w) KB.
-//   kNT: that KB is tile rows R = 32 p + 8 w + lane/8, physical chunk lane%8 of each row;
+// Stage fill.  Load p of wave w fills KB number (p kWaves + w) of the 32 KB operand tile.
+//   kNT: that KB is tile rows R = 8 (p kWaves + w) + lane/8, physical chunk lane%8 of each row;
 //        logical chunk = physical ^ ((R ^ (R >> 3)) & 7).
-//   kTN: that KB is contraction rows T = 8 p + 2 w + lane/32, 16-byte slot lane%32 of each;
-//        logical 64-byte block = physical block ^ (T & 3).
+//   kTN: that KB is contraction rows T = 2 (p kWaves + w) + lane/32, 16-byte slot lane%32 of
+//        each; logical 64-byte block = physical block ^ (T & 3).
 // ---------------------------------------------------------------------------------------------
 struct FillPtrs {
     const char* base_a;       // wave-uniform global byte address of the tile's first element
     const char* base_b;
     int64_t pstep_a, pstep_b; // wave-uniform byte distance between loads p and p + 1
-    uint32_t voff_a[2];       // per-lane byte offsets (even / odd p for kNT, identical for kTN)
+    uint32_t voff_a[2];       // per-lane byte offsets (even / odd p; they differ only for kNT with 4 waves)
     uint32_t voff_b[2];
 };
 
-template <bool kTN>
+template <bool kTN, int kWN>
 __device__ __forceinline__ FillPtrs make_fill(const uint16_t* A, const uint16_t* B, int64_t lda, int64_t ldb,
                                               int m0, int n0) {
+    constexpr int kWaves = Shape<kWN>::kWaves;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     FillPtrs f;
     if (kTN) {
-        const int T = 2 * w + (lane >> 5);                     // + 8 p
+        const int T = 2 * w + (lane >> 5);                     // + 2 kWaves p
         const int slot = lane & 31;
         const int blk = (slot >> 2) ^ (T & 3);
         const int col = blk * 32 + (slot & 3) * 8;             // element offset inside the 256-wide tile row
@@ -97,20 +113,20 @@ __device__ __forceinline__ FillPtrs make_fill(const uint16_t* A, const uint16_t*
         f.base_b = reinterpret_cast<const char*>(B + n0);
         f.voff_a[0] = f.voff_a[1] = uint32_t((int64_t(T) * lda + col) * 2);
         f.voff_b[0] = f.voff_b[1] = uint32_t((int64_t(T) * ldb + col) * 2);
-        f.pstep_a = 8 * lda * 2; f.pstep_b = 8 * ldb * 2;
+        f.pstep_a = 2 * kWaves * lda * 2; f.pstep_b = 2 * kWaves * ldb * 2;
     } else {
-        const int r = 8 * w + (lane >> 3);                     // + 32 p
+        const int r = 8 * w + (lane >> 3);                     // + 8 kWaves p
         const int pc = lane & 7;
         f.base_a = reinterpret_cast<const char*>(A + int64_t(m0) * lda);
         f.base_b = reinterpret_cast<const char*>(B + int64_t(n0) * ldb);
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {                          // p even / odd differ in bit 2 of the swizzle
-            const int R = r + 32 * q;
+        for (int q = 0; q < 2; ++q) {                          // p even / odd
+            const int R = r + 8 * kWaves * q;
             const int c = pc ^ ((R ^ (R >> 3)) & 7);
             f.voff_a[q] = uint32_t((int64_t(r) * lda + c * 8) * 2);
             f.voff_b[q] = uint32_t((int64_t(r) * ldb + c * 8) * 2);
         }
-        f.pstep_a = 32 * lda * 2; f.pstep_b = 32 * ldb * 2;
+        f.pstep_a = 8 * kWaves * lda * 2; f.pstep_b = 8 * kWaves * ldb * 2;
     }
     return f;
 }
@@ -131,21 +147,36 @@ __device__ __forceinline__ void wait_direct_loads() {
     __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0), other counters untouched
 }
 
-// Issue load number q (0..15) of a stage fill: even q fetch operand A, odd q operand B, load
-// p = q / 2.  ka / kb are the wave-uniform byte offsets of the contraction step to fetch;
+// Issue load number q (0 .. kLoads-1) of a stage fill: even q fetch operand A, odd q operand B,
+// load p = q / 2.  ka / kb are the wave-uniform byte offsets of the contraction step to fetch;
 // lds_wave_base is the LDS byte address of the stage plus 1 KB times the wave index.
-template <bool kTN, int q>
+template <bool kTN, int kWN, int q>
 __device__ __forceinline__ void fill_one(const FillPtrs& f, int64_t ka, int64_t kb, uint32_t lds_wave_base) {
     constexpr int p = q >> 1;
-    if ((q & 1) == 0) direct_load_16B<p * 4096>(f.base_a + ka + p * f.pstep_a, f.voff_a[p & 1], lds_wave_base);
-    else direct_load_16B<kTileBytes + p * 4096>(f.base_b + kb + p * f.pstep_b, f.voff_b[p & 1], lds_wave_base);
+    constexpr int kOff = p * Shape<kWN>::kWaves * 1024;
+    if ((q & 1) == 0) direct_load_16B<kOff>(f.base_a + ka + p * f.pstep_a, f.voff_a[p & 1], lds_wave_base);
+    else direct_load_16B<kTileBytes + kOff>(f.base_b + kb + p * f.pstep_b, f.voff_b[p & 1], lds_wave_base);
 }
 
-template <bool kTN, int q = 0, int end = 16>
-__device__ __forceinline__ void fill_stage(const FillPtrs& f, int64_t ka, int64_t kb, uint32_t lds_wave_base) {
+template <bool kTN, int kWN, int q, int end>
+__device__ __forceinline__ void fill_range(const FillPtrs& f, int64_t ka, int64_t kb, uint32_t lds_wave_base) {
     if constexpr (q < end) {
-        fill_one<kTN, q>(f, ka, kb, lds_wave_base);
-        fill_stage<kTN, q + 1, end>(f, ka, kb, lds_wave_base);
+        fill_one<kTN, kWN, q>(f, ka, kb, lds_wave_base);
+        fill_range<kTN, kWN, q + 1, end>(f, ka, kb, lds_wave_base);
+    }
+}
+
+// Run-time index -> compile-time load number (the LDS offset of a load is an immediate).
+template <bool kTN, int kWN>
+__device__ __forceinline__ void fill_switch(int load, const FillPtrs& f, int64_t ka, int64_t kb, uint32_t dst) {
+    switch (load) {
+#define TF_FILL_CASE(Q) case Q: if constexpr (Q < Shape<kWN>::kLoads) fill_one<kTN, kWN, Q>(f, ka, kb, dst); break;
+        TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
+        TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
+        TF_FILL_CASE(8) TF_FILL_CASE(9) TF_FILL_CASE(10) TF_FILL_CASE(11)
+        TF_FILL_CASE(12) TF_FILL_CASE(13) TF_FILL_CASE(14) TF_FILL_CASE(15)
+#undef TF_FILL_CASE
+        default: break;
     }
 }
 
@@ -153,14 +184,16 @@ __device__ __forceinline__ void fill_stage(const FillPtrs& f, int64_t ka, int64_
 // MFMA operand fetch for contraction step s (16 values) of the current stage.
 // Operand lane l holds row (l % 32) of a 32-row block and contraction values 8 (l / 32) .. + 7.
 // ---------------------------------------------------------------------------------------------
+template <int kWN>
 struct FragAddr {
-    int a[4], b[4];       // per-lane LDS byte offsets (inside a stage) of the 4 row blocks, step 0
+    int a[4], b[Shape<kWN>::kNJ];     // per-lane LDS byte offsets (inside a stage) of the row blocks, step 0
 };
 
-template <bool kTN>
-__device__ __forceinline__ FragAddr make_frag_addr(int wm, int wn) {
+template <bool kTN, int kWN>
+__device__ __forceinline__ FragAddr<kWN> make_frag_addr(int wm, int wn) {
+    constexpr int kNJ = Shape<kWN>::kNJ, kWaveN = Shape<kWN>::kWaveN;
     const int lane = threadIdx.x & 63;
-    FragAddr fa;
+    FragAddr<kWN> fa;
     if (kTN) {
         // 16-lane group G reads rows 8 (G / 2) + {0..3} (+4 for the second read) of the
         // contraction and columns 16 (G % 2) + {0..15} of the 32-row block; as a source lane
@@ -169,18 +202,21 @@ __device__ __forceinline__ FragAddr make_frag_addr(int wm, int wn) {
         const int x = ii >> 2;
         const int laneoff = (8 * (G >> 1) + x) * 512 + 32 * (G & 1) + 8 * (ii & 3);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            fa.a[i] = laneoff + wm * 256 + ((i ^ x) * 64);
-            fa.b[i] = kTileBytes + laneoff + wn * 256 + ((i ^ x) * 64);
-        }
+        for (int i = 0; i < 4; ++i) fa.a[i] = laneoff + (((wm * 4 + i) ^ x) * 64);
+#pragma unroll
+        for (int j = 0; j < kNJ; ++j) fa.b[j] = kTileBytes + laneoff + (((wn * kNJ + j) ^ x) * 64);
     } else {
         const int lrow = lane & 31, lhalf = lane >> 5;
+        // chunk (2 s + lhalf) ^ swz(row): the s-dependent part is XORed in at use
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int ra = wm * 128 + i * 32 + lrow, rb = wn * 128 + i * 32 + lrow;
-            // chunk (2 s + lhalf) ^ swz(row): the s-dependent part is XORed in at use
+            const int ra = wm * 128 + i * 32 + lrow;
             fa.a[i] = ra * 128 + ((lhalf ^ ((ra ^ (ra >> 3)) & 7)) << 4);
-            fa.b[i] = kTileBytes + rb * 128 + ((lhalf ^ ((rb ^ (rb >> 3)) & 7)) << 4);
+        }
+#pragma unroll
+        for (int j = 0; j < kNJ; ++j) {
+            const int rb = wn * kWaveN + j * 32 + lrow;
+            fa.b[j] = kTileBytes + rb * 128 + ((lhalf ^ ((rb ^ (rb >> 3)) & 7)) << 4);
         }
     }
     return fa;
@@ -200,8 +236,10 @@ __device__ __forceinline__ bf16x8 load_frag(const char* stage, int addr, int s) 
     }
 }
 
-template <bool kTN, bool kOutBf16, bool kAccumulate>
-__global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
+template <bool kTN, bool kOutBf16, bool kAccumulate, int kWN>
+__global__ __launch_bounds__(Shape<kWN>::kThreads) void gemm_mfma_kernel(GemmBatch batch) {
+    using S = Shape<kWN>;
+    constexpr int kNJ = S::kNJ;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
 
     const int lt = logical_tile(blockIdx.x, gridDim.x);
@@ -227,51 +265,50 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     const int64_t kstep_b = kTN ? int64_t(kBK) * ldb * 2 : kBK * 2;
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / kWN, wn = wave % kWN;
 
-    f32x16 acc[4][4];
+    f32x16 acc[4][kNJ];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < kNJ; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    const FillPtrs fp = make_fill<kTN>(A, B, lda, ldb, m0, n0);
-    const FragAddr fr = make_frag_addr<kTN>(wm, wn);
+    const FillPtrs fp = make_fill<kTN, kWN>(A, B, lda, ldb, m0, n0);
+    const FragAddr<kWN> fr = make_frag_addr<kTN, kWN>(wm, wn);
     const int nk = Kc / kBK;
 
     // LDS byte address of the dynamic shared array (a 32-bit LDS pointer is its byte offset),
-    // plus this wave's 1 KB slot inside every 4 KB group of a stage fill.
+    // plus this wave's 1 KB slot inside every group of kWaves KB of a stage fill.
     const uint32_t lds_wave_base = __builtin_amdgcn_readfirstlane(
         uint32_t(reinterpret_cast<uintptr_t>(TF_LPTR(lds))) + uint32_t(wave) * 1024u);
 
-    // prologue: stage 0 <- step 0, stage 1 <- step 1 (step 0 again if there is only one)
-    fill_stage<kTN>(fp, 0, 0, lds_wave_base);
+    // prologue: stage 0 <- step 0 completely, stage 1 <- first part of step 1 (the loop issues the rest)
+    fill_range<kTN, kWN, 0, S::kLoads>(fp, 0, 0, lds_wave_base);
     wait_direct_loads();
     __syncthreads();
     {
-        const int k1 = min(1, nk - 1);     // first part of stage 1; the loop issues the rest
-        fill_stage<kTN, 0, kLoadsStep3>(fp, k1 * kstep_a, k1 * kstep_b, lds_wave_base + kStageBytes);
+        const int k1 = min(1, nk - 1);
+        fill_range<kTN, kWN, 0, S::kLoadsStep3>(fp, k1 * kstep_a, k1 * kstep_b, lds_wave_base + kStageBytes);
     }
-    bf16x8 fa[2][4], fb[2][4];
+    bf16x8 fa[2][4], fb[2][kNJ];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        fa[0][i] = load_frag<kTN>(lds, fr.a[i], 0);
-        fb[0][i] = load_frag<kTN>(lds, fr.b[i], 0);
-    }
+    for (int i = 0; i < 4; ++i) fa[0][i] = load_frag<kTN>(lds, fr.a[i], 0);
+#pragma unroll
+    for (int j = 0; j < kNJ; ++j) fb[0][j] = load_frag<kTN>(lds, fr.b[j], 0);
 
     for (int kt = 0; kt < nk; ++kt) {
         const char* cur = lds + (kt & 1) * kStageBytes;
         const char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
         const uint32_t cur_fill = lds_wave_base + (kt & 1) * kStageBytes;
+        const uint32_t nxt_fill = lds_wave_base + ((kt + 1) & 1) * kStageBytes;
         // Contraction step fetched into `cur` once everybody is done reading it; past the end
         // the last step is fetched again (into a stage nobody reads any more), which keeps the
         // loop body free of branches.
         const int kf = min(kt + 2, nk - 1), kf1 = min(kt + 1, nk - 1);
         const int64_t ka = kf * kstep_a, kb = kf * kstep_b;          // fetched during step 3, into `cur`
         const int64_t ka1 = kf1 * kstep_a, kb1 = kf1 * kstep_b;      // rest of the previous fill, into `nxt`
-        const uint32_t nxt_fill = lds_wave_base + ((kt + 1) & 1) * kStageBytes;
 
         // Issue order below is pinned with scheduling fences.
         __builtin_amdgcn_sched_barrier(0);
@@ -288,40 +325,27 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
             const char* rd = s == 3 ? nxt : cur;     // step 3 reads step 0 of the next stage
             const int rs = s == 3 ? 0 : s + 1;
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int i = q >> 2, j = q & 3;
+            for (int q = 0; q < S::kMfmaPerStep; ++q) {
+                const int i = q / kNJ, j = q % kNJ;
                 // D rows <- n (B operand rows), D columns <- m: a lane then owns 4 consecutive n
                 // of one output row m, i.e. 4 contiguous elements of row-major C.
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s & 1][j], fa[s & 1][i], acc[i][j], 0, 0, 0);
-                if (q < 8) {
-                    if (q & 1) fb[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.b[q >> 1], rs);
-                    else       fa[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.a[q >> 1], rs);
+                if (q < S::kReadsPerStep) {
+                    // operand order A0 B0 A1 B1 ... then the remaining A blocks
+                    if (q < 2 * kNJ) {
+                        if (q & 1) fb[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.b[q >> 1], rs);
+                        else       fa[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.a[q >> 1], rs);
+                    } else {
+                        fa[(s + 1) & 1][q - kNJ] = load_frag<kTN>(rd, fr.a[q - kNJ], rs);
+                    }
                 }
-                {
-                    // Which direct-to-LDS load (0..15, -1 = none) follows MFMA q of step s.  The
-                    // loads of one stage fill are spread over step 3 (right after the barrier that
-                    // frees the stage) and steps 0..1 of the next stage's turn, so that the
-                    // texture-address unit, which all four waves share, is never asked for more
-                    // than it can take while the matrix cores run.
-                    constexpr int n3 = kLoadsStep3, n0 = kLoadsStep0, n1 = 16 - n3 - n0;
-                    const int cnt = s == 3 ? n3 : s == 0 ? n0 : s == 1 ? n1 : 0;
-                    const int first = s == 3 ? 0 : s == 0 ? n3 : n3 + n0;
-                    int load = -1;
-                    if (cnt > 0) {
-                        const int stride = 16 / cnt;
-                        if (q % stride == 0 && q / stride < cnt) load = first + q / stride;
-                    }
-                    const int64_t la = s == 3 ? ka : ka1, lb = s == 3 ? kb : kb1;
-                    const uint32_t dst = s == 3 ? cur_fill : nxt_fill;
-                    switch (load) {
-#define TF_FILL_CASE(Q) case Q: fill_one<kTN, Q>(fp, la, lb, dst); break;
-                        TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
-                        TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
-                        TF_FILL_CASE(8) TF_FILL_CASE(9) TF_FILL_CASE(10) TF_FILL_CASE(11)
-                        TF_FILL_CASE(12) TF_FILL_CASE(13) TF_FILL_CASE(14) TF_FILL_CASE(15)
-#undef TF_FILL_CASE
-                        default: break;
-                    }
+                // The loads of one stage fill follow every other MFMA of step 3 (right after the
+                // barrier that frees the stage) and of step 0 of the next stage's turn, so that
+                // the texture-address unit, which the waves share, is never asked for more than
+                // it can take while the matrix cores run.
+                if ((s == 3 || s == 0) && (q & 1) == 0 && q / 2 < S::kLoadsStep3) {
+                    if (s == 3) fill_switch<kTN, kWN>(q / 2, fp, ka, kb, cur_fill);
+                    else        fill_switch<kTN, kWN>(S::kLoadsStep3 + q / 2, fp, ka1, kb1, nxt_fill);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -330,56 +354,64 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     wait_direct_loads();      // nothing of this workgroup may still be in flight towards LDS
 
     // epilogue: acc[i][j][4g + e] is C[m][n] with m = m0 + wm*128 + i*32 + lane%32,
-    // n = n0 + wn*128 + j*32 + 8g + 4*(lane/32) + e.  A lane's values are scattered over the
-    // tile, so each wave first turns its 128 x 128 block around in its own 32 KB quarter of the
-    // (now idle) LDS and then writes whole rows: 16 lanes x 16 bytes cover 256 contiguous bytes.
+    // n = n0 + wn*kWaveN + j*32 + 8g + 4*(lane/32) + e.  A lane's values are scattered over the
+    // tile, so each wave first turns its block around in its own share of the (now idle) LDS
+    // and then writes whole rows.
     __syncthreads();                                   // every wave is done reading the stages
-    char* wlds = lds + wave * 32768;
+    char* wlds = lds + wave * S::kEpiBytes;
     const int lrow = lane & 31, lhalf = lane >> 5;
+    constexpr int kChunks = S::kWaveN / 4;             // 4-element chunks per row of the wave's block: 32 or 16
     if (kOutBf16) {
-        // [128 rows][32 chunks of 8 bytes], chunk index XORed with the row to spread the banks
+        // [128 rows][kChunks chunks of 8 bytes]; the chunk index is XORed with a row number so
+        // that the 32 rows written by one instruction fall into different banks
+        constexpr int kPitch = S::kWaveN * 2;
+        const int xw = kChunks == 32 ? lrow : (lrow >> 1);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < kNJ; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int m = i * 32 + lrow, c = 8 * j + 2 * g + lhalf;
-                    *reinterpret_cast<U2*>(wlds + m * 256 + ((c ^ lrow) << 3)) =
+                    *reinterpret_cast<U2*>(wlds + m * kPitch + ((c ^ xw) << 3)) =
                         U2{f32x2_to_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]),
                            f32x2_to_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3])};
                 }
-        const int cb = lane & 15, rsub = lane >> 4;    // 16-byte column block, row inside a group of 4
-        uint16_t* Cw = static_cast<uint16_t*>(P.C) + int64_t(m0 + wm * 128) * N + n0 + wn * 128 + cb * 8;
+        constexpr int kLanesPerRow = kPitch / 16, kRowsPerInstr = 64 / kLanesPerRow;
+        const int cb = lane % kLanesPerRow, rsub = lane / kLanesPerRow;   // 16-byte column block, row in group
+        uint16_t* Cw = static_cast<uint16_t*>(P.C) + int64_t(m0 + wm * 128) * N + n0 + wn * S::kWaveN + cb * 8;
 #pragma unroll 8
-        for (int it = 0; it < 32; ++it) {
-            const int m = it * 4 + rsub, x = m & 31;
-            // chunks 2cb and 2cb+1 sit in one aligned 16-byte pair, swapped when the row is odd
-            U4 v = *reinterpret_cast<const U4*>(wlds + m * 256 + (((2 * cb) ^ (x & 30)) << 3));
+        for (int it = 0; it < 128 / kRowsPerInstr; ++it) {
+            const int m = it * kRowsPerInstr + rsub;
+            const int x = kChunks == 32 ? (m & 31) : ((m >> 1) & 15);
+            // chunks 2cb and 2cb+1 sit in one aligned 16-byte pair, swapped when x is odd
+            U4 v = *reinterpret_cast<const U4*>(wlds + m * kPitch + (((2 * cb) ^ (x & ~1)) << 3));
             if (x & 1) v = U4{v.z, v.w, v.x, v.y};
             *reinterpret_cast<U4*>(Cw + int64_t(m) * N) = v;
         }
     } else {
-        // fp32: two passes of 64 rows, [64 rows][32 chunks of 16 bytes]
+        // fp32: two passes of 64 rows, [64 rows][kChunks chunks of 16 bytes]
+        constexpr int kPitch = S::kWaveN * 4;
+        constexpr int kLanesPerRow = kPitch / 16, kRowsPerInstr = 64 / kLanesPerRow;
+        const int cb = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
 #pragma unroll
             for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < kNJ; ++j)
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const int i = 2 * h + ii;
                         const int m = ii * 32 + lrow, c = 8 * j + 2 * g + lhalf;
-                        *reinterpret_cast<F4*>(wlds + m * 512 + ((c ^ lrow) << 4)) =
+                        *reinterpret_cast<F4*>(wlds + m * kPitch + ((c ^ (lrow & (kChunks - 1))) << 4)) =
                             F4{acc[i][j][4 * g + 0], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
                     }
-            const int cb = lane & 31, rsub = lane >> 5;    // 16-byte column block, row inside a pair
-            float* Cw = static_cast<float*>(P.C) + int64_t(m0 + wm * 128 + h * 64) * N + n0 + wn * 128 + cb * 4;
+            float* Cw = static_cast<float*>(P.C) + int64_t(m0 + wm * 128 + h * 64) * N + n0 + wn * S::kWaveN + cb * 4;
 #pragma unroll 8
-            for (int it = 0; it < 32; ++it) {
-                const int m = it * 2 + rsub;
-                F4 v = *reinterpret_cast<const F4*>(wlds + m * 512 + ((cb ^ (m & 31)) << 4));
+            for (int it = 0; it < 64 / kRowsPerInstr; ++it) {
+                const int m = it * kRowsPerInstr + rsub;
+                F4 v = *reinterpret_cast<const F4*>(wlds + m * kPitch + ((cb ^ (m & (kChunks - 1))) << 4));
                 F4* dst = reinterpret_cast<F4*>(Cw + int64_t(m) * N);
                 if (kAccumulate) v += *dst;
                 *dst = v;
@@ -390,11 +422,12 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
 
 template <bool kTN, bool kOutBf16, bool kAccumulate>
 hipError_t launch_one(hipStream_t stream, const GemmBatch& batch) {
-    auto kern = gemm_mfma_kernel<kTN, kOutBf16, kAccumulate>;
+    constexpr int kWN = TF_GEMM_WN;
+    auto kern = gemm_mfma_kernel<kTN, kOutBf16, kAccumulate, kWN>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(batch.total_tiles), dim3(kThreads), kLdsBytes, stream, batch);
+    hipLaunchKernelGGL(kern, dim3(batch.total_tiles), dim3(Shape<kWN>::kThreads), kLdsBytes, stream, batch);
     return hipGetLastError();
 }
 
