@@ -122,6 +122,26 @@ def stage_backward(shapes: Sequence[tuple], T: int, W, X, dY, freeze_mask,
         raise RuntimeError("oracle_stage_backward failed")
 
 
+def sample_dx(dY, W, ts, ks) -> np.ndarray:
+    """Single elements of the input gradient, one by one: dX[t, k] = sum_n dY[t, n] W[k, n]
+    (Sec. 3.2.1, activation-gradient component).  dY [T, N] and W [K, N] may be float32 or
+    float64 arrays; every product and sum is done in float64.  For outputs too large to
+    compute in full."""
+    out = np.empty(len(ts), dtype=np.float64)
+    for i, (t, k) in enumerate(zip(ts, ks)):
+        out[i] = np.dot(np.asarray(dY[t, :], dtype=np.float64), np.asarray(W[k, :], dtype=np.float64))
+    return out
+
+
+def sample_dw(X, dY, ks, ns) -> np.ndarray:
+    """Single elements of the weight gradient: G[k, n] = sum_t X[t, k] dY[t, n]
+    (Sec. 3.2.1, parameter-gradient component), in float64."""
+    out = np.empty(len(ks), dtype=np.float64)
+    for i, (k, n) in enumerate(zip(ks, ns)):
+        out[i] = np.dot(np.asarray(X[:, k], dtype=np.float64), np.asarray(dY[:, n], dtype=np.float64))
+    return out
+
+
 def masked_adamw(p, m, v, grad, *, step: int, lr: float, beta1: float, beta2: float,
                  eps: float, weight_decay: float, grad_scale: float = 1.0,
                  p_lowp=None, elem_frozen=None, ema=None, ema_abs=None,

@@ -136,11 +136,15 @@ __device__ __forceinline__ FillPtrs make_fill(const uint16_t* A, const uint16_t*
 // Written as inline assembly so that the compiler's wait-count insertion does not treat every
 // later LDS read as dependent on it (it would drain the load queue before each transpose read);
 // completion is awaited explicitly with wait_direct_loads() before the stage barrier.
+// The assembly must leave SCC alone: the compiler is free to place it between the two halves
+// of one of its own 64-bit scalar additions (s_add_u32 / s_addc_u32), and a clobbered carry
+// sends the high word of a global address off by one as soon as the addition crosses a
+// 4 GiB boundary.  Hence s_mov_b32 for M0, with the LDS address added up outside.
 template <int kLdsOff>
 __device__ __forceinline__ void direct_load_16B(const char* gbase, uint32_t voff, uint32_t lds_wave_base) {
-    asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, %3"
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_wave_base), "n"(kLdsOff), "v"(voff), "s"(gbase)
+                 : "s"(lds_wave_base + uint32_t(kLdsOff)), "v"(voff), "s"(gbase)
                  : "memory");
 }
 __device__ __forceinline__ void wait_direct_loads() {

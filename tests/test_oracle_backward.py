@@ -164,3 +164,18 @@ def test_planted_transpose_would_be_caught():
     dX, dW = _run([(k, n)], T, W, X, dY, [0])
     assert not np.allclose(dX[0], dY[0] @ W[0])          # W, not W^T: wrong
     assert not np.allclose(dW[0], dY[0].T @ X[0])        # dY^T X: wrong
+
+
+def test_sampled_elements_equal_the_full_oracle():
+    # the one-by-one form used for outputs too large to compute in full
+    rs = np.random.default_rng(8)
+    k, n, T = 9, 13, 17
+    W = [rs.standard_normal((k, n))]; X = [rs.standard_normal((T, k))]; dY = [rs.standard_normal((T, n))]
+    dX, dW = _run([(k, n)], T, W, X, dY, [0])
+    ts = rs.integers(0, T, 40); ks = rs.integers(0, k, 40); ns = rs.integers(0, n, 40)
+    np.testing.assert_allclose(oracle.sample_dx(dY[0], W[0], ts, ks), dX[0][ts, ks], rtol=1e-13, atol=1e-14)
+    np.testing.assert_allclose(oracle.sample_dw(X[0], dY[0], ks, ns), dW[0][ks, ns], rtol=1e-13, atol=1e-14)
+    # float32 inputs are up-cast exactly, not rounded
+    got = oracle.sample_dx(dY[0].astype(np.float32), W[0].astype(np.float32), ts, ks)
+    exp = (dY[0].astype(np.float32).astype(np.float64) @ W[0].astype(np.float32).astype(np.float64).T)[ts, ks]
+    np.testing.assert_allclose(got, exp, rtol=1e-13, atol=1e-14)
