@@ -394,31 +394,46 @@ __global__ __launch_bounds__(Shape<kWN>::kThreads) void gemm_mfma_kernel(GemmBat
             *reinterpret_cast<U4*>(Cw + int64_t(m) * N) = v;
         }
     } else {
-        // fp32: two passes of 64 rows, [64 rows][kChunks chunks of 16 bytes]
+        // fp32: two passes of 64 rows, [64 rows][kChunks chunks of 16 bytes].  When accumulating,
+        // the old values are fetched a batch of 16 row groups ahead (into registers the main loop
+        // no longer needs), so that their HBM latency overlaps the LDS turn-around and the stores.
         constexpr int kPitch = S::kWaveN * 4;
         constexpr int kLanesPerRow = kPitch / 16, kRowsPerInstr = 64 / kLanesPerRow;
+        constexpr int kIt = 64 / kRowsPerInstr;            // row groups per pass: 32 or 16
+        constexpr int kBatch = 16, kBatchesPerPass = kIt / kBatch, kBatches = 2 * kBatchesPerPass;
         const int cb = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
+        float* Cw = static_cast<float*>(P.C) + int64_t(m0 + wm * 128) * N + n0 + wn * S::kWaveN + cb * 4;
+        // row of the wave's block handled by row group `it` of batch `b`
+        auto row_of = [&](int b, int it) { return (b / kBatchesPerPass) * 64 + ((b % kBatchesPerPass) * kBatch + it) * kRowsPerInstr + rsub; };
+        F4 old[2][kBatch];
+        auto fetch_old = [&](int b) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+            for (int it = 0; it < kBatch; ++it) old[b & 1][it] = *reinterpret_cast<const F4*>(Cw + int64_t(row_of(b, it)) * N);
+        };
+        if (kAccumulate) fetch_old(0);
 #pragma unroll
-            for (int ii = 0; ii < 2; ++ii)
+        for (int b = 0; b < kBatches; ++b) {
+            if (kAccumulate && b + 1 < kBatches) fetch_old(b + 1);
+            if (b % kBatchesPerPass == 0) {
+                const int h = b / kBatchesPerPass;
 #pragma unroll
-                for (int j = 0; j < kNJ; ++j)
+                for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int i = 2 * h + ii;
-                        const int m = ii * 32 + lrow, c = 8 * j + 2 * g + lhalf;
-                        *reinterpret_cast<F4*>(wlds + m * kPitch + ((c ^ (lrow & (kChunks - 1))) << 4)) =
-                            F4{acc[i][j][4 * g + 0], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                    }
-            float* Cw = static_cast<float*>(P.C) + int64_t(m0 + wm * 128 + h * 64) * N + n0 + wn * S::kWaveN + cb * 4;
-#pragma unroll 8
-            for (int it = 0; it < 64 / kRowsPerInstr; ++it) {
-                const int m = it * kRowsPerInstr + rsub;
+                    for (int j = 0; j < kNJ; ++j)
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const int i = 2 * h + ii;
+                            const int m = ii * 32 + lrow, c = 8 * j + 2 * g + lhalf;
+                            *reinterpret_cast<F4*>(wlds + m * kPitch + ((c ^ (lrow & (kChunks - 1))) << 4)) =
+                                F4{acc[i][j][4 * g + 0], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                        }
+            }
+#pragma unroll
+            for (int it = 0; it < kBatch; ++it) {
+                const int row = row_of(b, it), m = row & 63;
                 F4 v = *reinterpret_cast<const F4*>(wlds + m * kPitch + ((cb ^ (m & (kChunks - 1))) << 4));
-                F4* dst = reinterpret_cast<F4*>(Cw + int64_t(m) * N);
-                if (kAccumulate) v += *dst;
-                *dst = v;
+                if (kAccumulate) v += old[b & 1][it];
+                *reinterpret_cast<F4*>(Cw + int64_t(row) * N) = v;
             }
         }
     }
