@@ -267,6 +267,10 @@ def main():
                 if 0.0 < s["r"] < 1.0 and s["phi"] > 0:
                     # time saved relative to what the skipped dW FLOP fraction would ideally save
                     s["eta_backward"] = (b0 - s["backward_ms"]) / (s["phi"] * (b0 - b1))
+                    d0 = t_by_r[0.0]["kernels"].get("dw_mfma", {}).get("avg_ms")
+                    dr = s["kernels"].get("dw_mfma", {}).get("avg_ms")
+                    if d0 and dr:   # the same slope on the dW kernel alone (dX does not depend on r)
+                        s["eta_dw_kernel"] = (d0 - dr) / (s["phi"] * d0)
 
     # ---- roofline of the dominant kernel: the grouped input-gradient GEMM ----
     dx = head["kernels"].get("dx_mfma")

@@ -51,7 +51,10 @@ struct Shape {
     static constexpr int kReadsPerStep = 4 + kNJ;           // operand fragments per step: 8 or 6
     static constexpr int kLoadsPerOperand = 32 / kWaves;    // 1 KB loads per wave, operand and stage: 8 or 4
     static constexpr int kLoads = 2 * kLoadsPerOperand;     // 16 or 8
-    static constexpr int kLoadsStep3 = kLoads / 2;          // issued in step 3; the rest in the next step 0
+    // Loads of a stage fill issued in step 3 / in the next step 0 (the rest, if any, in step 1).
+    // Half and half measured best; later loads arrive too late for the stage barrier.
+    static constexpr int kLoadsStep3 = kLoads / 2;
+    static constexpr int kLoadsStep0 = kLoads - kLoadsStep3;
     static constexpr int kEpiBytes = kLdsBytes / kWaves;    // LDS per wave for the epilogue: 32 or 16 KB
 };
 
@@ -343,13 +346,22 @@ __global__ __launch_bounds__(Shape<kWN>::kThreads) void gemm_mfma_kernel(GemmBat
                         fa[(s + 1) & 1][q - kNJ] = load_frag<kTN>(rd, fr.a[q - kNJ], rs);
                     }
                 }
-                // The loads of one stage fill follow every other MFMA of step 3 (right after the
-                // barrier that frees the stage) and of step 0 of the next stage's turn, so that
-                // the texture-address unit, which the waves share, is never asked for more than
-                // it can take while the matrix cores run.
-                if ((s == 3 || s == 0) && (q & 1) == 0 && q / 2 < S::kLoadsStep3) {
-                    if (s == 3) fill_switch<kTN, kWN>(q / 2, fp, ka, kb, cur_fill);
-                    else        fill_switch<kTN, kWN>(S::kLoadsStep3 + q / 2, fp, ka1, kb1, nxt_fill);
+                // The loads of one stage fill are spread over step 3 (right after the barrier that
+                // frees the stage) and steps 0 and 1 of the next stage's turn, so that the
+                // texture-address unit, which the waves share, is never asked for more than it
+                // can take while the matrix cores run.
+                {
+                    constexpr int n3 = S::kLoadsStep3, n0 = S::kLoadsStep0, n1 = S::kLoads - n3 - n0;
+                    const int cnt = s == 3 ? n3 : s == 0 ? n0 : s == 1 ? n1 : 0;
+                    const int first = s == 3 ? 0 : s == 0 ? n3 : n3 + n0;
+                    if (cnt > 0) {
+                        // spread `cnt` loads evenly over the MFMA slots of this step
+                        const int before = (q * cnt) / S::kMfmaPerStep, after = ((q + 1) * cnt) / S::kMfmaPerStep;
+                        if (after > before) {
+                            if (s == 3) fill_switch<kTN, kWN>(first + before, fp, ka, kb, cur_fill);
+                            else        fill_switch<kTN, kWN>(first + before, fp, ka1, kb1, nxt_fill);
+                        }
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
