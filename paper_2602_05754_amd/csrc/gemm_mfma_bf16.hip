@@ -5,17 +5,21 @@
 // Only tensors that are not frozen are ever listed in a kTN batch, so a frozen
 // tensor's dW tiles cost nothing and its buffers are never touched.
 //
-// One 256 x 256 output tile per workgroup.  The waves form a 2 x kWN grid
-// (kWN = 2: 4 waves of 128 x 128, 256 accumulators per lane; kWN = 4: 8 waves of
-// 128 x 64, 128 accumulators per lane, two waves per SIMD), each wave owning
-// 4 x (8 / kWN) MFMA 32x32x16 tiles.  The contraction advances 64 at a time
-// through two LDS stages of 64 KB that are filled by direct global->LDS loads
-// (no register staging): while the matrix cores work on one stage the next one
-// is in flight.  A stage is consumed in four steps of 16; the operands of step
-// s + 1 are read from LDS while the MFMAs of step s issue, the stage barrier
-// sits after the reads of the last step, and the first operands of the next
-// stage are read during the last step, so neither LDS latency nor the barrier
-// leaves the matrix cores idle.
+// Persistent workgroups: one per compute unit, each walking every gridDim.x-th
+// 256 x 256 output tile of the launch.  Four waves in a 2 x 2 grid, 128 x 128 per
+// wave = 4 x 4 MFMA 32x32x16 tiles, 256 accumulators per lane.  The contraction
+// advances 64 at a time through two LDS stages of 64 KB that are filled by direct
+// global->LDS loads (no register staging).  The fills form ONE stream over all
+// tiles of the workgroup: while the matrix cores finish a tile, the first two
+// contraction steps of the next tile are already in flight, so a tile switch costs
+// the epilogue and nothing else - no drain, no refill, no new workgroup.
+// A stage is consumed in four steps of 16; the operands of step s + 1 are read
+// from LDS while the MFMAs of step s issue, the stage barrier sits after the reads
+// of the last step, and the first operands of the next stage are read during the
+// last step, so neither LDS latency nor the barrier leaves the matrix cores idle.
+// The first step of a tile multiplies into a zero constant instead of clearing
+// 256 registers.  The epilogue turns 32-row blocks around in 8 KB of LDS per wave
+// that lies beyond the two stages, so it never collides with the fills in flight.
 //
 //   kNT stage: [256 rows][64 contraction] per operand, 16-byte chunks of a row
 //              XOR-swizzled; MFMA operands are plain 128-bit LDS reads.
@@ -26,37 +30,27 @@
 // so a swizzle is applied by choosing which global address each lane fetches.
 #include "tf_internal.h"
 
+#include <type_traits>
+
 namespace tf {
 namespace {
 
 constexpr int kBM = 256, kBN = 256, kBK = 64;
+constexpr int kWaves = 4, kThreads = 64 * kWaves;
 constexpr int kTileBytes = kBM * kBK * 2;             // 32 KB per operand per stage
-constexpr int kStageBytes = 2 * kTileBytes;           // A + B
-constexpr int kLdsBytes = 2 * kStageBytes;            // two stages = 128 KB
+// LDS map: [A stage 0][A stage 1][B stage 0][B stage 1][epilogue areas].
+constexpr int kStageStride = kTileBytes;              // from stage 0 to stage 1 of one operand
+constexpr int kOperandB = 2 * kTileBytes;             // from operand A to operand B of one stage
+constexpr int kStagesBytes = 4 * kTileBytes;          // two stages of two operands = 128 KB
+constexpr int kEpiBytes = 8192;                       // per wave, beyond the stages
+constexpr int kLdsBytes = kStagesBytes + kWaves * kEpiBytes;   // 160 KB: all of a compute unit's LDS
 constexpr int kGroupM = 8;                            // tile rows per L2 locality group
 constexpr int kXcds = 8;
 constexpr int kXcdRun = 32;                           // consecutive logical tiles kept on one XCD
-
-#ifndef TF_GEMM_WN
-#define TF_GEMM_WN 2
-#endif
-
-template <int kWN>
-struct Shape {
-    static constexpr int kWaves = 2 * kWN;                  // 4 or 8
-    static constexpr int kThreads = 64 * kWaves;
-    static constexpr int kWaveN = kBN / kWN;                // columns per wave: 128 or 64
-    static constexpr int kNJ = kWaveN / 32;                 // MFMA column blocks per wave: 4 or 2
-    static constexpr int kMfmaPerStep = 4 * kNJ;            // 16 or 8
-    static constexpr int kReadsPerStep = 4 + kNJ;           // operand fragments per step: 8 or 6
-    static constexpr int kLoadsPerOperand = 32 / kWaves;    // 1 KB loads per wave, operand and stage: 8 or 4
-    static constexpr int kLoads = 2 * kLoadsPerOperand;     // 16 or 8
-    // Loads of a stage fill issued in step 3 / in the next step 0 (the rest, if any, in step 1).
-    // Half and half measured best; later loads arrive too late for the stage barrier.
-    static constexpr int kLoadsStep3 = kLoads / 2;
-    static constexpr int kLoadsStep0 = kLoads - kLoadsStep3;
-    static constexpr int kEpiBytes = kLdsBytes / kWaves;    // LDS per wave for the epilogue: 32 or 16 KB
-};
+constexpr int kLoads = 16;                            // 1 KB loads per wave and stage fill (8 per operand)
+// Loads of a stage fill issued in step 3 / in the next step 0.  Half and half measured
+// best; later loads arrive too late for the stage barrier.
+constexpr int kLoadsStep3 = kLoads / 2;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -75,9 +69,20 @@ __device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
 }
 
-// blockIdx -> logical tile.  Hardware hands workgroup b to XCD b % 8; runs of kXcdRun
-// consecutive logical tiles are kept on one XCD (shared L2), runs go round-robin over
-// the XCDs so that all of them work on the same part of the tile list.
+// Accumulator register -> vector register, at this point of the program.  Left to itself the
+// register allocator copies all 256 accumulators of a wave at the head of the epilogue, which
+// inside the tile loop is more vector registers than are free.
+__device__ __forceinline__ float acc_read(float a) {
+    float v;
+    asm("v_accvgpr_read_b32 %0, %1" : "=v"(v) : "a"(a));
+    return v;
+}
+
+// Virtual block index -> logical tile.  Hardware hands workgroup b to XCD b % 8, and the
+// virtual blocks b, b + gridDim.x, ... of one workgroup keep that XCD (gridDim.x is a
+// multiple of 8 whenever a workgroup gets more than one tile).  Runs of kXcdRun consecutive
+// logical tiles are kept on one XCD (shared L2), runs go round-robin over the XCDs so that
+// all of them work on the same part of the tile list.
 __device__ __forceinline__ int logical_tile(int b, int nb) {
     const int span = kXcds * kXcdRun;
     const int full = (nb / span) * span;
@@ -86,42 +91,57 @@ __device__ __forceinline__ int logical_tile(int b, int nb) {
     return ((idx / kXcdRun) * kXcds + xcd) * kXcdRun + idx % kXcdRun;
 }
 
+struct TilePos { int pi, m0, n0; };
+
+// Logical tile -> problem and tile origin.  `pi` is where the search starts: a workgroup
+// visits its tiles in increasing order, so the problem index never goes back.
+__device__ __forceinline__ TilePos locate_tile(const GemmBatch& batch, int lt, int pi) {
+    while (pi + 1 < batch.n_problems && lt >= batch.p[pi + 1].tile_start) ++pi;
+    const GemmProblem& P = batch.p[pi];
+    const int tiles_m = P.M / kBM, tiles_n = P.N / kBN;
+    int t = lt - P.tile_start;
+    const int per_group = kGroupM * tiles_n;
+    const int first_m = (t / per_group) * kGroupM;
+    const int gsz = min(tiles_m - first_m, kGroupM);
+    t %= per_group;
+    return TilePos{pi, (first_m + t % gsz) * kBM, (t / gsz) * kBN};
+}
+
 // ---------------------------------------------------------------------------------------------
-// Stage fill.  Load p of wave w fills KB number (p kWaves + w) of the 32 KB operand tile.
-//   kNT: that KB is tile rows R = 8 (p kWaves + w) + lane/8, physical chunk lane%8 of each row;
+// Stage fill.  Load p of wave w fills KB number (4 p + w) of the 32 KB operand tile.
+//   kNT: that KB is tile rows R = 8 (4 p + w) + lane/8, physical chunk lane%8 of each row;
 //        logical chunk = physical ^ ((R ^ (R >> 3)) & 7).
-//   kTN: that KB is contraction rows T = 2 (p kWaves + w) + lane/32, 16-byte slot lane%32 of
+//   kTN: that KB is contraction rows T = 2 (4 p + w) + lane/32, 16-byte slot lane%32 of
 //        each; logical 64-byte block = physical block ^ (T & 3).
 // ---------------------------------------------------------------------------------------------
-struct FillPtrs {
-    const char* base_a;       // wave-uniform global byte address of the tile's first element
-    const char* base_b;
+struct Fill {
+    const char* ga;           // wave-uniform global byte address: tile origin + contraction offset
+    const char* gb;
     int64_t pstep_a, pstep_b; // wave-uniform byte distance between loads p and p + 1
-    uint32_t voff_a[2];       // per-lane byte offsets (even / odd p; they differ only for kNT with 4 waves)
+    uint32_t voff_a[2];       // per-lane byte offsets (even / odd p; they differ only for kNT)
     uint32_t voff_b[2];
 };
 
-template <bool kTN, int kWN>
-__device__ __forceinline__ FillPtrs make_fill(const uint16_t* A, const uint16_t* B, int64_t lda, int64_t ldb,
-                                              int m0, int n0) {
-    constexpr int kWaves = Shape<kWN>::kWaves;
+template <bool kTN>
+__device__ __forceinline__ Fill make_fill(const uint16_t* A, const uint16_t* B, int64_t lda, int64_t ldb,
+                                          int m0, int n0) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    FillPtrs f;
+    Fill f;
     if (kTN) {
-        const int T = 2 * w + (lane >> 5);                     // + 2 kWaves p
+        const int T = 2 * w + (lane >> 5);                     // + 8 p
         const int slot = lane & 31;
         const int blk = (slot >> 2) ^ (T & 3);
         const int col = blk * 32 + (slot & 3) * 8;             // element offset inside the 256-wide tile row
-        f.base_a = reinterpret_cast<const char*>(A + m0);
-        f.base_b = reinterpret_cast<const char*>(B + n0);
+        f.ga = reinterpret_cast<const char*>(A + m0);
+        f.gb = reinterpret_cast<const char*>(B + n0);
         f.voff_a[0] = f.voff_a[1] = uint32_t((int64_t(T) * lda + col) * 2);
         f.voff_b[0] = f.voff_b[1] = uint32_t((int64_t(T) * ldb + col) * 2);
         f.pstep_a = 2 * kWaves * lda * 2; f.pstep_b = 2 * kWaves * ldb * 2;
     } else {
-        const int r = 8 * w + (lane >> 3);                     // + 8 kWaves p
+        const int r = 8 * w + (lane >> 3);                     // + 32 p
         const int pc = lane & 7;
-        f.base_a = reinterpret_cast<const char*>(A + int64_t(m0) * lda);
-        f.base_b = reinterpret_cast<const char*>(B + int64_t(n0) * ldb);
+        f.ga = reinterpret_cast<const char*>(A + int64_t(m0) * lda);
+        f.gb = reinterpret_cast<const char*>(B + int64_t(n0) * ldb);
 #pragma unroll
         for (int q = 0; q < 2; ++q) {                          // p even / odd
             const int R = r + 8 * kWaves * q;
@@ -139,51 +159,86 @@ __device__ __forceinline__ FillPtrs make_fill(const uint16_t* A, const uint16_t*
 // Written as inline assembly so that the compiler's wait-count insertion does not treat every
 // later LDS read as dependent on it (it would drain the load queue before each transpose read);
 // completion is awaited explicitly with wait_direct_loads() before the stage barrier.
-// The assembly must leave SCC alone: the compiler is free to place it between the two halves
-// of one of its own 64-bit scalar additions (s_add_u32 / s_addc_u32), and a clobbered carry
-// sends the high word of a global address off by one as soon as the addition crosses a
-// 4 GiB boundary.  Hence s_mov_b32 for M0, with the LDS address added up outside.
+// The addition sets SCC, and the compiler is free to place the statement between the two
+// halves of one of its own 64-bit scalar additions (s_add_u32 / s_addc_u32) unless it is told:
+// a clobbered carry sends the high word of a global address off by one as soon as the addition
+// crosses a 4 GiB boundary.  Hence the "scc" clobber; the build scans the generated code for
+// inline assembly between a producer and a consumer of SCC and refuses it.
 template <int kLdsOff>
 __device__ __forceinline__ void direct_load_16B(const char* gbase, uint32_t voff, uint32_t lds_wave_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+    asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
-                 : "s"(lds_wave_base + uint32_t(kLdsOff)), "v"(voff), "s"(gbase)
-                 : "memory");
+                 : "s"(lds_wave_base), "v"(voff), "s"(gbase), "n"(kLdsOff)
+                 : "memory", "scc");
 }
 __device__ __forceinline__ void wait_direct_loads() {
     __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0), other counters untouched
 }
 
-// Issue load number q (0 .. kLoads-1) of a stage fill: even q fetch operand A, odd q operand B,
-// load p = q / 2.  ka / kb are the wave-uniform byte offsets of the contraction step to fetch;
-// lds_wave_base is the LDS byte address of the stage plus 1 KB times the wave index.
-template <bool kTN, int kWN, int q>
-__device__ __forceinline__ void fill_one(const FillPtrs& f, int64_t ka, int64_t kb, uint32_t lds_wave_base) {
+// Running global addresses of a stage fill: one load per operand and call of fill_next.
+struct FillRun {
+    const char* a;
+    const char* b;
+};
+// Start at load pair p0 (load p of an operand fetches KB number 4 p + w of its tile).
+template <int p0>
+__device__ __forceinline__ FillRun fill_begin(const Fill& f) {
+    return FillRun{f.ga + p0 * f.pstep_a, f.gb + p0 * f.pstep_b};
+}
+// Issue load number q (0 .. kLoads-1) of a stage fill: even q fetch operand A, odd q operand
+// B, load pair p = q / 2.  lds_wave_base is the LDS byte address of the stage (of operand A)
+// plus 1 KB times the wave index.
+template <int q>
+__device__ __forceinline__ void fill_next(const Fill& f, FillRun& run, uint32_t lds_wave_base) {
     constexpr int p = q >> 1;
-    constexpr int kOff = p * Shape<kWN>::kWaves * 1024;
-    if ((q & 1) == 0) direct_load_16B<kOff>(f.base_a + ka + p * f.pstep_a, f.voff_a[p & 1], lds_wave_base);
-    else direct_load_16B<kTileBytes + kOff>(f.base_b + kb + p * f.pstep_b, f.voff_b[p & 1], lds_wave_base);
+    constexpr int kOff = p * kWaves * 1024;
+    if ((q & 1) == 0) { direct_load_16B<kOff>(run.a, f.voff_a[p & 1], lds_wave_base); run.a += f.pstep_a; }
+    else              { direct_load_16B<kOperandB + kOff>(run.b, f.voff_b[p & 1], lds_wave_base); run.b += f.pstep_b; }
 }
 
-template <bool kTN, int kWN, int q, int end>
-__device__ __forceinline__ void fill_range(const FillPtrs& f, int64_t ka, int64_t kb, uint32_t lds_wave_base) {
+template <int q, int end>
+__device__ __forceinline__ void fill_range(const Fill& f, FillRun& run, uint32_t lds_wave_base) {
     if constexpr (q < end) {
-        fill_one<kTN, kWN, q>(f, ka, kb, lds_wave_base);
-        fill_range<kTN, kWN, q + 1, end>(f, ka, kb, lds_wave_base);
+        fill_next<q>(f, run, lds_wave_base);
+        fill_range<q + 1, end>(f, run, lds_wave_base);
     }
 }
 
-// Run-time index -> compile-time load number (the LDS offset of a load is an immediate).
-template <bool kTN, int kWN>
-__device__ __forceinline__ void fill_switch(int load, const FillPtrs& f, int64_t ka, int64_t kb, uint32_t dst) {
-    switch (load) {
-#define TF_FILL_CASE(Q) case Q: if constexpr (Q < Shape<kWN>::kLoads) fill_one<kTN, kWN, Q>(f, ka, kb, dst); break;
-        TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
-        TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
-        TF_FILL_CASE(8) TF_FILL_CASE(9) TF_FILL_CASE(10) TF_FILL_CASE(11)
-        TF_FILL_CASE(12) TF_FILL_CASE(13) TF_FILL_CASE(14) TF_FILL_CASE(15)
-#undef TF_FILL_CASE
-        default: break;
+// The fill stream of a workgroup: contraction steps of its tiles, one after the other.
+struct StreamPos {
+    int64_t kstep_a, kstep_b;  // byte advance per contraction step of 64
+    int kt, nk;                // step inside the tile, steps of the tile
+    int vb;                    // virtual block index of the tile
+    int pi;                    // its problem
+};
+
+template <bool kTN>
+__device__ __forceinline__ void stream_set_tile(StreamPos& c, Fill& f, const GemmBatch& batch, int vb) {
+    const TilePos tp = locate_tile(batch, logical_tile(vb, batch.total_tiles), c.pi);
+    const GemmProblem& P = batch.p[tp.pi];
+    const int64_t lda = kTN ? P.M : P.Kc, ldb = kTN ? P.N : P.Kc;
+    f = make_fill<kTN>(static_cast<const uint16_t*>(P.A), static_cast<const uint16_t*>(P.B), lda, ldb, tp.m0, tp.n0);
+    c.kstep_a = kTN ? int64_t(kBK) * lda * 2 : kBK * 2;
+    c.kstep_b = kTN ? int64_t(kBK) * ldb * 2 : kBK * 2;
+    c.kt = 0; c.nk = P.Kc / kBK; c.vb = vb; c.pi = tp.pi;
+}
+
+// Move `f` (the step the position stands on) to the next step of the stream, in two parts.
+// stream_guess is branch-free: it assumes that the tile goes on.  stream_settle puts things
+// right when the tile has ended.  Past the end of the workgroup's last tile the position stays
+// where it is: the last step is then fetched again, into a stage nobody reads any more, which
+// keeps the main loop free of special cases.
+__device__ __forceinline__ void stream_guess(const StreamPos& c, Fill& f) {
+    f.ga += c.kstep_a; f.gb += c.kstep_b;
+}
+template <bool kTN>
+__device__ __forceinline__ void stream_settle(StreamPos& c, Fill& f, const GemmBatch& batch) {
+    if (__builtin_expect(c.kt + 1 < c.nk, 1)) {
+        ++c.kt;
+    } else if (c.vb + int(gridDim.x) < batch.total_tiles) {
+        stream_set_tile<kTN>(c, f, batch, c.vb + int(gridDim.x));
+    } else {
+        f.ga -= c.kstep_a; f.gb -= c.kstep_b;
     }
 }
 
@@ -191,16 +246,14 @@ __device__ __forceinline__ void fill_switch(int load, const FillPtrs& f, int64_t
 // MFMA operand fetch for contraction step s (16 values) of the current stage.
 // Operand lane l holds row (l % 32) of a 32-row block and contraction values 8 (l / 32) .. + 7.
 // ---------------------------------------------------------------------------------------------
-template <int kWN>
 struct FragAddr {
-    int a[4], b[Shape<kWN>::kNJ];     // per-lane LDS byte offsets (inside a stage) of the row blocks, step 0
+    int a[4], b[4];     // per-lane LDS byte offsets (stage 0) of the row blocks, step 0
 };
 
-template <bool kTN, int kWN>
-__device__ __forceinline__ FragAddr<kWN> make_frag_addr(int wm, int wn) {
-    constexpr int kNJ = Shape<kWN>::kNJ, kWaveN = Shape<kWN>::kWaveN;
+template <bool kTN>
+__device__ __forceinline__ FragAddr make_frag_addr(int wm, int wn) {
     const int lane = threadIdx.x & 63;
-    FragAddr<kWN> fa;
+    FragAddr fa;
     if (kTN) {
         // 16-lane group G reads rows 8 (G / 2) + {0..3} (+4 for the second read) of the
         // contraction and columns 16 (G % 2) + {0..15} of the 32-row block; as a source lane
@@ -211,7 +264,7 @@ __device__ __forceinline__ FragAddr<kWN> make_frag_addr(int wm, int wn) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) fa.a[i] = laneoff + (((wm * 4 + i) ^ x) * 64);
 #pragma unroll
-        for (int j = 0; j < kNJ; ++j) fa.b[j] = kTileBytes + laneoff + (((wn * kNJ + j) ^ x) * 64);
+        for (int j = 0; j < 4; ++j) fa.b[j] = kOperandB + laneoff + (((wn * 4 + j) ^ x) * 64);
     } else {
         const int lrow = lane & 31, lhalf = lane >> 5;
         // chunk (2 s + lhalf) ^ swz(row): the s-dependent part is XORed in at use
@@ -221,9 +274,9 @@ __device__ __forceinline__ FragAddr<kWN> make_frag_addr(int wm, int wn) {
             fa.a[i] = ra * 128 + ((lhalf ^ ((ra ^ (ra >> 3)) & 7)) << 4);
         }
 #pragma unroll
-        for (int j = 0; j < kNJ; ++j) {
-            const int rb = wn * kWaveN + j * 32 + lrow;
-            fa.b[j] = kTileBytes + rb * 128 + ((lhalf ^ ((rb ^ (rb >> 3)) & 7)) << 4);
+        for (int j = 0; j < 4; ++j) {
+            const int rb = wn * 128 + j * 32 + lrow;
+            fa.b[j] = kOperandB + rb * 128 + ((lhalf ^ ((rb ^ (rb >> 3)) & 7)) << 4);
         }
     }
     return fa;
@@ -243,80 +296,151 @@ __device__ __forceinline__ bf16x8 load_frag(const char* stage, int addr, int s) 
     }
 }
 
-template <bool kTN, bool kOutBf16, bool kAccumulate, int kWN>
-__global__ __launch_bounds__(Shape<kWN>::kThreads) void gemm_mfma_kernel(GemmBatch batch) {
-    using S = Shape<kWN>;
-    constexpr int kNJ = S::kNJ;
+// ---------------------------------------------------------------------------------------------
+// Epilogue of one tile, per wave: acc[i][j][4g + e] is C[m][n] with
+//   m = row0 + i*32 + lane%32,  n = col0 + j*32 + 8g + 4*(lane/32) + e.
+// A lane's values are scattered over the block, so the wave turns 8 KB pieces around in its
+// own LDS area `wlds` (32 rows of 256 bytes) and writes whole 256-byte row segments.
+// ---------------------------------------------------------------------------------------------
+template <bool kOutBf16, bool kAccumulate>
+__device__ __forceinline__ void store_block(const f32x16 (&acc)[4][4], char* wlds, void* C, int64_t N,
+                                            int row0, int col0) {
+    int lane = threadIdx.x & 63;
+    // The epilogue sits inside the tile loop.  Its per-lane addresses are loop invariants, and
+    // kept in registers across the contraction steps they would crowd out the operands: make
+    // the lane number opaque so that they are worked out again for every tile instead.
+    asm volatile("" : "+v"(lane));
+    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int cb = lane & 15, rsub = lane >> 4;        // 16-byte column block, row inside a group of 4
+    if (kOutBf16) {
+        // one pass per 32-row block: [32 rows][32 chunks of 8 bytes]; the chunk index is XORed
+        // with the row so that the 32 rows written by one instruction fall into different banks
+        uint16_t* Cw = static_cast<uint16_t*>(C) + int64_t(row0) * N + col0 + cb * 8;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            // fences keep the passes apart: hoisting the register reads of later passes over
+            // this one would need more registers than a lane has
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int c = 8 * j + 2 * g + lhalf;
+                    *reinterpret_cast<U2*>(wlds + lrow * 256 + ((c ^ lrow) << 3)) =
+                        U2{f32x2_to_bf16x2(acc_read(acc[i][j][4 * g + 0]), acc_read(acc[i][j][4 * g + 1])),
+                           f32x2_to_bf16x2(acc_read(acc[i][j][4 * g + 2]), acc_read(acc[i][j][4 * g + 3]))};
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int m = it * 4 + rsub;
+                // chunks 2cb and 2cb+1 sit in one aligned 16-byte pair, swapped when m is odd
+                U4 v = *reinterpret_cast<const U4*>(wlds + m * 256 + (((2 * cb) ^ (m & ~1)) << 3));
+                if (m & 1) v = U4{v.z, v.w, v.x, v.y};
+                *reinterpret_cast<U4*>(Cw + int64_t(i * 32 + m) * N) = v;
+            }
+        }
+    } else {
+        // fp32: one pass per 32 rows x 64 columns: [32 rows][16 chunks of 16 bytes].  When
+        // accumulating, the old values are fetched two passes ahead so that their HBM latency
+        // overlaps the LDS turn-around and the stores.
+        float* Cw = static_cast<float*>(C) + int64_t(row0) * N + col0 + cb * 4;
+        auto gaddr = [&](int p, int it) { return Cw + int64_t((p >> 1) * 32 + it * 4 + rsub) * N + (p & 1) * 64; };
+        F4 old[3][8];
+        auto fetch_old = [&](int p) {
+#pragma unroll
+            for (int it = 0; it < 8; ++it) old[p % 3][it] = *reinterpret_cast<const F4*>(gaddr(p, it));
+        };
+        if (kAccumulate) { fetch_old(0); fetch_old(1); }
+#pragma unroll
+        for (int p = 0; p < 8; ++p) {
+            if (kAccumulate && p + 2 < 8) fetch_old(p + 2);
+            const int i = p >> 1, jh = p & 1;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int c = 8 * jj + 2 * g + lhalf;
+                    const f32x16& a = acc[i][2 * jh + jj];
+                    *reinterpret_cast<F4*>(wlds + lrow * 256 + ((c ^ (lrow & 15)) << 4)) =
+                        F4{a[4 * g + 0], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]};
+                }
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int m = it * 4 + rsub;
+                F4 v = *reinterpret_cast<const F4*>(wlds + m * 256 + ((cb ^ (m & 15)) << 4));
+                if (kAccumulate) v += old[p % 3][it];
+                *reinterpret_cast<F4*>(gaddr(p, it)) = v;
+            }
+        }
+    }
+}
+
+template <bool kTN, bool kOutBf16, bool kAccumulate>
+__global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
 
-    const int lt = logical_tile(blockIdx.x, gridDim.x);
-    int pi = 0;
-    for (int i = 1; i < batch.n_problems; ++i)
-        if (lt >= batch.p[i].tile_start) pi = i;
-    const GemmProblem& P = batch.p[pi];
-    const int M = P.M, N = P.N, Kc = P.Kc;
-    const int tiles_m = M / kBM, tiles_n = N / kBN;
-    int t = lt - P.tile_start;
-    const int per_group = kGroupM * tiles_n;
-    const int first_m = (t / per_group) * kGroupM;
-    const int gsz = min(tiles_m - first_m, kGroupM);
-    t %= per_group;
-    const int m0 = (first_m + t % gsz) * kBM;
-    const int n0 = (t / gsz) * kBN;
-
-    const uint16_t* A = static_cast<const uint16_t*>(P.A);
-    const uint16_t* B = static_cast<const uint16_t*>(P.B);
-    const int64_t lda = kTN ? M : Kc, ldb = kTN ? N : Kc;
-    // byte advance of the global pointers per contraction step of 64
-    const int64_t kstep_a = kTN ? int64_t(kBK) * lda * 2 : kBK * 2;
-    const int64_t kstep_b = kTN ? int64_t(kBK) * ldb * 2 : kBK * 2;
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave / kWN, wn = wave % kWN;
-
-    f32x16 acc[4][kNJ];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < kNJ; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
-    const FillPtrs fp = make_fill<kTN, kWN>(A, B, lda, ldb, m0, n0);
-    const FragAddr<kWN> fr = make_frag_addr<kTN, kWN>(wm, wn);
-    const int nk = Kc / kBK;
+    const int wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int stride = int(gridDim.x), total = batch.total_tiles;
 
     // LDS byte address of the dynamic shared array (a 32-bit LDS pointer is its byte offset),
-    // plus this wave's 1 KB slot inside every group of kWaves KB of a stage fill.
+    // plus this wave's 1 KB slot inside every group of 4 KB of a stage fill.
     const uint32_t lds_wave_base = __builtin_amdgcn_readfirstlane(
         uint32_t(reinterpret_cast<uintptr_t>(TF_LPTR(lds))) + uint32_t(wave) * 1024u);
+    char* wlds = lds + kStagesBytes + wave * kEpiBytes;
+    const FragAddr fr = make_frag_addr<kTN>(wm, wn);
 
-    // prologue: stage 0 <- step 0 completely, stage 1 <- first part of step 1 (the loop issues the rest)
-    fill_range<kTN, kWN, 0, S::kLoads>(fp, 0, 0, lds_wave_base);
+    // Fill stream.  Step g of the stream goes to stage g % 2.  Its loads are issued in two
+    // halves: the first during the last quarter of step g - 2 (right after the barrier that
+    // frees the stage), the second during the first quarter of step g - 1.
+    StreamPos pos;
+    Fill ahead2;                       // step g + 2 while step g is consumed: first half to issue
+    Fill ahead1;                       // step g + 1: second half to issue
+    pos.pi = 0;
+    stream_set_tile<kTN>(pos, ahead1, batch, int(blockIdx.x));
+    {
+        FillRun run = fill_begin<0>(ahead1);
+        fill_range<0, kLoads>(ahead1, run, lds_wave_base);                   // step 0, all of it
+    }
+    stream_guess(pos, ahead1);
+    stream_settle<kTN>(pos, ahead1, batch);                                  // ahead1 = step 1
     wait_direct_loads();
     __syncthreads();
     {
-        const int k1 = min(1, nk - 1);
-        fill_range<kTN, kWN, 0, S::kLoadsStep3>(fp, k1 * kstep_a, k1 * kstep_b, lds_wave_base + kStageBytes);
+        FillRun run = fill_begin<0>(ahead1);
+        fill_range<0, kLoadsStep3>(ahead1, run, lds_wave_base + kStageStride);   // step 1, first half
     }
-    bf16x8 fa[2][4], fb[2][kNJ];
+    ahead2 = ahead1;
+    stream_guess(pos, ahead2);
+    stream_settle<kTN>(pos, ahead2, batch);                                  // ahead2 = step 2
+
+    // The tile being consumed.
+    int cvb = int(blockIdx.x);
+    TilePos ct = locate_tile(batch, logical_tile(cvb, total), 0);
+    int cnk = batch.p[ct.pi].Kc / kBK;
+
+    f32x16 acc[4][4];
+    bf16x8 fa[2][4], fb[2][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) fa[0][i] = load_frag<kTN>(lds, fr.a[i], 0);
 #pragma unroll
-    for (int j = 0; j < kNJ; ++j) fb[0][j] = load_frag<kTN>(lds, fr.b[j], 0);
+    for (int j = 0; j < 4; ++j) fb[0][j] = load_frag<kTN>(lds, fr.b[j], 0);
 
-    for (int kt = 0; kt < nk; ++kt) {
-        const char* cur = lds + (kt & 1) * kStageBytes;
-        const char* nxt = lds + ((kt + 1) & 1) * kStageBytes;
-        const uint32_t cur_fill = lds_wave_base + (kt & 1) * kStageBytes;
-        const uint32_t nxt_fill = lds_wave_base + ((kt + 1) & 1) * kStageBytes;
-        // Contraction step fetched into `cur` once everybody is done reading it; past the end
-        // the last step is fetched again (into a stage nobody reads any more), which keeps the
-        // loop body free of branches.
-        const int kf = min(kt + 2, nk - 1), kf1 = min(kt + 1, nk - 1);
-        const int64_t ka = kf * kstep_a, kb = kf * kstep_b;          // fetched during step 3, into `cur`
-        const int64_t ka1 = kf1 * kstep_a, kb1 = kf1 * kstep_b;      // rest of the previous fill, into `nxt`
-
+    int g = 0;
+    // One contraction step of 64.  `first_tag` says whether it opens a tile: then its first
+    // 16 MFMAs take a zero constant as their addend.
+    auto contraction_step = [&](auto first_tag) {
+        constexpr bool kFirst = decltype(first_tag)::value;
+        const int h = g & 1;
+        const char* cur = lds + h * kStageStride;
+        const char* nxt = lds + (1 - h) * kStageStride;
+        const uint32_t cur_fill = lds_wave_base + h * kStageStride;
+        const uint32_t nxt_fill = lds_wave_base + (1 - h) * kStageStride;
+        FillRun run;
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         // Issue order below is pinned with scheduling fences.
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -332,133 +456,88 @@ __global__ __launch_bounds__(Shape<kWN>::kThreads) void gemm_mfma_kernel(GemmBat
             const char* rd = s == 3 ? nxt : cur;     // step 3 reads step 0 of the next stage
             const int rs = s == 3 ? 0 : s + 1;
 #pragma unroll
-            for (int q = 0; q < S::kMfmaPerStep; ++q) {
-                const int i = q / kNJ, j = q % kNJ;
+            for (int q = 0; q < 16; ++q) {
+                const int i = q >> 2, j = q & 3;
                 // D rows <- n (B operand rows), D columns <- m: a lane then owns 4 consecutive n
                 // of one output row m, i.e. 4 contiguous elements of row-major C.
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s & 1][j], fa[s & 1][i], acc[i][j], 0, 0, 0);
-                if (q < S::kReadsPerStep) {
-                    // operand order A0 B0 A1 B1 ... then the remaining A blocks
-                    if (q < 2 * kNJ) {
-                        if (q & 1) fb[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.b[q >> 1], rs);
-                        else       fa[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.a[q >> 1], rs);
-                    } else {
-                        fa[(s + 1) & 1][q - kNJ] = load_frag<kTN>(rd, fr.a[q - kNJ], rs);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s & 1][j], fa[s & 1][i],
+                                                                   (kFirst && s == 0) ? zero : acc[i][j], 0, 0, 0);
+                if (q < 8) {
+                    // operand order A0 B0 A1 B1 A2 B2 A3 B3
+                    if (q & 1) fb[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.b[q >> 1], rs);
+                    else       fa[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.a[q >> 1], rs);
+                }
+                // The loads of one stage fill are spread over two quarters, so that the
+                // texture-address unit, which the waves share, is never asked for more than it
+                // can take while the matrix cores run: one load after every second MFMA.
+                if (s == 0 && q == 0) run = fill_begin<kLoadsStep3 / 2>(ahead1);
+                if (s == 3 && q == 0) run = fill_begin<0>(ahead2);
+                if (s == 0 && (q & 1)) {
+                    switch (q >> 1) {
+#define TF_FILL_CASE(Q) case Q: fill_next<kLoadsStep3 + Q>(ahead1, run, nxt_fill); break;
+                        TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
+                        TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
+#undef TF_FILL_CASE
                     }
                 }
-                // The loads of one stage fill are spread over step 3 (right after the barrier that
-                // frees the stage) and steps 0 and 1 of the next stage's turn, so that the
-                // texture-address unit, which the waves share, is never asked for more than it
-                // can take while the matrix cores run.
-                {
-                    constexpr int n3 = S::kLoadsStep3, n0 = S::kLoadsStep0, n1 = S::kLoads - n3 - n0;
-                    const int cnt = s == 3 ? n3 : s == 0 ? n0 : s == 1 ? n1 : 0;
-                    const int first = s == 3 ? 0 : s == 0 ? n3 : n3 + n0;
-                    if (cnt > 0) {
-                        // spread `cnt` loads evenly over the MFMA slots of this step
-                        const int before = (q * cnt) / S::kMfmaPerStep, after = ((q + 1) * cnt) / S::kMfmaPerStep;
-                        if (after > before) {
-                            if (s == 3) fill_switch<kTN, kWN>(first + before, fp, ka, kb, cur_fill);
-                            else        fill_switch<kTN, kWN>(first + before, fp, ka1, kb1, nxt_fill);
-                        }
+                // step g + 1 is on its way in full: what was two steps ahead is one step ahead now
+                if (s == 1 && q == 8) ahead1 = ahead2;
+                if (s == 3 && (q & 1)) {
+                    switch (q >> 1) {
+#define TF_FILL_CASE(Q) case Q: fill_next<Q>(ahead2, run, cur_fill); break;
+                        TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
+                        TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
+#undef TF_FILL_CASE
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        stream_guess(pos, ahead2);
+    };
+
+    // Tiles of this workgroup; the inner loop is the hot one and has a single taken branch
+    // per contraction step.
+    for (;;) {
+        contraction_step(std::true_type{});
+        stream_settle<kTN>(pos, ahead2, batch);
+        ++g;
+        for (int kt = 1; kt < cnk; ++kt) {
+            contraction_step(std::false_type{});
+            stream_settle<kTN>(pos, ahead2, batch);
+            ++g;
+        }
+        const GemmProblem& P = batch.p[ct.pi];
+        store_block<kOutBf16, kAccumulate>(acc, wlds, P.C, P.N, ct.m0 + wm * 128, ct.n0 + wn * 128);
+        cvb += stride;
+        if (cvb >= total) break;
+        ct = locate_tile(batch, logical_tile(cvb, total), ct.pi);
+        cnk = batch.p[ct.pi].Kc / kBK;
     }
     wait_direct_loads();      // nothing of this workgroup may still be in flight towards LDS
+}
 
-    // epilogue: acc[i][j][4g + e] is C[m][n] with m = m0 + wm*128 + i*32 + lane%32,
-    // n = n0 + wn*kWaveN + j*32 + 8g + 4*(lane/32) + e.  A lane's values are scattered over the
-    // tile, so each wave first turns its block around in its own share of the (now idle) LDS
-    // and then writes whole rows.
-    __syncthreads();                                   // every wave is done reading the stages
-    char* wlds = lds + wave * S::kEpiBytes;
-    const int lrow = lane & 31, lhalf = lane >> 5;
-    constexpr int kChunks = S::kWaveN / 4;             // 4-element chunks per row of the wave's block: 32 or 16
-    if (kOutBf16) {
-        // [128 rows][kChunks chunks of 8 bytes]; the chunk index is XORed with a row number so
-        // that the 32 rows written by one instruction fall into different banks
-        constexpr int kPitch = S::kWaveN * 2;
-        const int xw = kChunks == 32 ? lrow : (lrow >> 1);
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int j = 0; j < kNJ; ++j)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int m = i * 32 + lrow, c = 8 * j + 2 * g + lhalf;
-                    *reinterpret_cast<U2*>(wlds + m * kPitch + ((c ^ xw) << 3)) =
-                        U2{f32x2_to_bf16x2(acc[i][j][4 * g + 0], acc[i][j][4 * g + 1]),
-                           f32x2_to_bf16x2(acc[i][j][4 * g + 2], acc[i][j][4 * g + 3])};
-                }
-        constexpr int kLanesPerRow = kPitch / 16, kRowsPerInstr = 64 / kLanesPerRow;
-        const int cb = lane % kLanesPerRow, rsub = lane / kLanesPerRow;   // 16-byte column block, row in group
-        uint16_t* Cw = static_cast<uint16_t*>(P.C) + int64_t(m0 + wm * 128) * N + n0 + wn * S::kWaveN + cb * 8;
-#pragma unroll 8
-        for (int it = 0; it < 128 / kRowsPerInstr; ++it) {
-            const int m = it * kRowsPerInstr + rsub;
-            const int x = kChunks == 32 ? (m & 31) : ((m >> 1) & 15);
-            // chunks 2cb and 2cb+1 sit in one aligned 16-byte pair, swapped when x is odd
-            U4 v = *reinterpret_cast<const U4*>(wlds + m * kPitch + (((2 * cb) ^ (x & ~1)) << 3));
-            if (x & 1) v = U4{v.z, v.w, v.x, v.y};
-            *reinterpret_cast<U4*>(Cw + int64_t(m) * N) = v;
-        }
-    } else {
-        // fp32: two passes of 64 rows, [64 rows][kChunks chunks of 16 bytes].  When accumulating,
-        // the old values are fetched a batch of 16 row groups ahead (into registers the main loop
-        // no longer needs), so that their HBM latency overlaps the LDS turn-around and the stores.
-        constexpr int kPitch = S::kWaveN * 4;
-        constexpr int kLanesPerRow = kPitch / 16, kRowsPerInstr = 64 / kLanesPerRow;
-        constexpr int kIt = 64 / kRowsPerInstr;            // row groups per pass: 32 or 16
-        constexpr int kBatch = 16, kBatchesPerPass = kIt / kBatch, kBatches = 2 * kBatchesPerPass;
-        const int cb = lane % kLanesPerRow, rsub = lane / kLanesPerRow;
-        float* Cw = static_cast<float*>(P.C) + int64_t(m0 + wm * 128) * N + n0 + wn * S::kWaveN + cb * 4;
-        // row of the wave's block handled by row group `it` of batch `b`
-        auto row_of = [&](int b, int it) { return (b / kBatchesPerPass) * 64 + ((b % kBatchesPerPass) * kBatch + it) * kRowsPerInstr + rsub; };
-        F4 old[2][kBatch];
-        auto fetch_old = [&](int b) {
-#pragma unroll
-            for (int it = 0; it < kBatch; ++it) old[b & 1][it] = *reinterpret_cast<const F4*>(Cw + int64_t(row_of(b, it)) * N);
-        };
-        if (kAccumulate) fetch_old(0);
-#pragma unroll
-        for (int b = 0; b < kBatches; ++b) {
-            if (kAccumulate && b + 1 < kBatches) fetch_old(b + 1);
-            if (b % kBatchesPerPass == 0) {
-                const int h = b / kBatchesPerPass;
-#pragma unroll
-                for (int ii = 0; ii < 2; ++ii)
-#pragma unroll
-                    for (int j = 0; j < kNJ; ++j)
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const int i = 2 * h + ii;
-                            const int m = ii * 32 + lrow, c = 8 * j + 2 * g + lhalf;
-                            *reinterpret_cast<F4*>(wlds + m * kPitch + ((c ^ (lrow & (kChunks - 1))) << 4)) =
-                                F4{acc[i][j][4 * g + 0], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                        }
-            }
-#pragma unroll
-            for (int it = 0; it < kBatch; ++it) {
-                const int row = row_of(b, it), m = row & 63;
-                F4 v = *reinterpret_cast<const F4*>(wlds + m * kPitch + ((cb ^ (m & (kChunks - 1))) << 4));
-                if (kAccumulate) v += old[b & 1][it];
-                *reinterpret_cast<F4*>(Cw + int64_t(row) * N) = v;
-            }
-        }
+int compute_units() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+        cached[dev] = n;
     }
+    return cached[dev];
 }
 
 template <bool kTN, bool kOutBf16, bool kAccumulate>
 hipError_t launch_one(hipStream_t stream, const GemmBatch& batch) {
-    constexpr int kWN = TF_GEMM_WN;
-    auto kern = gemm_mfma_kernel<kTN, kOutBf16, kAccumulate, kWN>;
+    auto kern = gemm_mfma_kernel<kTN, kOutBf16, kAccumulate>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3(batch.total_tiles), dim3(Shape<kWN>::kThreads), kLdsBytes, stream, batch);
+    // one workgroup per compute unit (a workgroup takes all of a unit's LDS and registers)
+    const int grid = batch.total_tiles < compute_units() ? batch.total_tiles : compute_units();
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsBytes, stream, batch);
     return hipGetLastError();
 }
 

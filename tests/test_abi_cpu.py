@@ -121,3 +121,46 @@ def test_scores_and_frozen_count_match_the_oracle_rule():
     for L, r in itertools.product([1, 7, 14, 28, 56, 100], [0, 0.1, 0.2, 0.25, 0.3, 0.4, 0.5, 0.6, 0.7, 0.75, 0.8, 0.9, 1.0]):
         assert tf.tf_num_frozen(r, L) == oracle.n_frozen(r, L), (L, r)
     assert tf.tf_num_frozen(0.1 * 3, 10) == 3 and tf.tf_num_frozen(-1.0, 5) == 0 and tf.tf_num_frozen(2.0, 5) == 5
+
+
+def test_scan_for_inline_assembly_between_scc_writer_and_reader():
+    """The build refuses GEMM code in which an inline-assembly block (the direct-to-LDS load
+    sets SCC) sits between a scalar instruction that writes SCC and one that reads it."""
+    from paper_2602_05754_amd.build import scc_hazards
+    split_carry = """
+kernel_a:
+	s_add_u32 s0, s1, s2
+	;;#ASMSTART
+	s_add_u32 m0, s3, 0x100
+	s_nop 0
+	global_load_lds_dwordx4 v1, s[4:5]
+	;;#ASMEND
+	s_addc_u32 s4, s5, 0
+"""
+    fine = """
+kernel_b:
+	;;#ASMSTART
+	s_add_u32 m0, s3, 0x100
+	;;#ASMEND
+	s_add_u32 s0, s1, s2
+	s_mov_b32 s9, 0
+	v_add_u32_e32 v1, v2, v3
+	s_addc_u32 s4, s5, 0
+	;;#ASMSTART
+	s_add_u32 m0, s3, 0x200
+	;;#ASMEND
+	s_cmp_lt_i32 s1, s2
+	s_cbranch_scc1 .LBB0_1
+"""
+    branch_on_stale = """
+kernel_c:
+	s_cmp_lt_i32 s1, s2
+	;;#ASMSTART
+	s_add_u32 m0, s3, 0x100
+	;;#ASMEND
+	s_mov_b32 s7, s8
+	s_cbranch_scc1 .LBB0_1
+"""
+    assert [(f, ins.split()[0]) for f, _, ins in scc_hazards(split_carry)] == [("kernel_a", "s_addc_u32")]
+    assert scc_hazards(fine) == []
+    assert [(f, ins.split()[0]) for f, _, ins in scc_hazards(branch_on_stale)] == [("kernel_c", "s_cbranch_scc1")]
