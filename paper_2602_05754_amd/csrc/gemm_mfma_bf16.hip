@@ -313,44 +313,67 @@ __device__ __forceinline__ void store_block(const f32x16 (&acc)[4][4], char* wld
     const int lrow = lane & 31, lhalf = lane >> 5;
     const int cb = lane & 15, rsub = lane >> 4;        // 16-byte column block, row inside a group of 4
     if (kOutBf16) {
-        // one pass per 32-row block: [32 rows][32 chunks of 8 bytes]; the chunk index is XORed
-        // with the row so that the 32 rows written by one instruction fall into different banks
+        // One pass per 32-row block: [32 rows][32 chunks of 8 bytes]; the chunk index is XORed
+        // with the row so that the 32 rows written by one instruction fall into different banks.
+        // Software pipeline: the accumulators of pass i + 1 are read and rounded in between the
+        // global stores of pass i, whose rate (the four waves share one path to memory) sets the
+        // pace.  The stores are non-temporal: the output is not read again by this kernel, and
+        // left in L2 it would push out the operand panels that the other workgroups still fetch.
         uint16_t* Cw = static_cast<uint16_t*>(C) + int64_t(row0) * N + col0 + cb * 8;
+        U2 pk[16];                         // one pass, rounded: pk[4 j + g] is chunk 8 j + 2 g + lhalf of row lrow
+        auto round_piece = [&](int i, int k) {      // two of the sixteen chunks of pass i
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            // fences keep the passes apart: hoisting the register reads of later passes over
-            // this one would need more registers than a lane has
+            for (int gg = 0; gg < 2; ++gg) {
+                const int j = k >> 1, g = (k & 1) * 2 + gg;
+                pk[4 * j + g] = U2{f32x2_to_bf16x2(acc_read(acc[i][j][4 * g + 0]), acc_read(acc[i][j][4 * g + 1])),
+                                   f32x2_to_bf16x2(acc_read(acc[i][j][4 * g + 2]), acc_read(acc[i][j][4 * g + 3]))};
+            }
+        };
+        auto to_lds = [&]() {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                __builtin_amdgcn_sched_barrier(0);
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const int c = 8 * j + 2 * g + lhalf;
-                    *reinterpret_cast<U2*>(wlds + lrow * 256 + ((c ^ lrow) << 3)) =
-                        U2{f32x2_to_bf16x2(acc_read(acc[i][j][4 * g + 0]), acc_read(acc[i][j][4 * g + 1])),
-                           f32x2_to_bf16x2(acc_read(acc[i][j][4 * g + 2]), acc_read(acc[i][j][4 * g + 3]))};
+                    *reinterpret_cast<U2*>(wlds + lrow * 256 + ((c ^ lrow) << 3)) = pk[4 * j + g];
                 }
+        };
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) round_piece(0, k);
+        to_lds();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            __builtin_amdgcn_sched_barrier(0);
+            U4 v[8];
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int m = it * 4 + rsub;
+                // chunks 2cb and 2cb+1 sit in one aligned 16-byte pair, swapped when m is odd
+                v[it] = *reinterpret_cast<const U4*>(wlds + m * 256 + (((2 * cb) ^ (m & ~1)) << 3));
             }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int it = 0; it < 8; ++it) {
                 const int m = it * 4 + rsub;
-                // chunks 2cb and 2cb+1 sit in one aligned 16-byte pair, swapped when m is odd
-                U4 v = *reinterpret_cast<const U4*>(wlds + m * 256 + (((2 * cb) ^ (m & ~1)) << 3));
-                if (m & 1) v = U4{v.z, v.w, v.x, v.y};
-                *reinterpret_cast<U4*>(Cw + int64_t(i * 32 + m) * N) = v;
+                const U4 w = (m & 1) ? U4{v[it].z, v[it].w, v[it].x, v[it].y} : v[it];
+                __builtin_nontemporal_store(w, reinterpret_cast<U4*>(Cw + int64_t(i * 32 + m) * N));
+                if (i < 3) round_piece(i + 1, it);
+                __builtin_amdgcn_sched_barrier(0);
             }
+            if (i < 3) to_lds();
         }
     } else {
         // fp32: one pass per 32 rows x 64 columns: [32 rows][16 chunks of 16 bytes].  When
         // accumulating, the old values are fetched two passes ahead so that their HBM latency
-        // overlaps the LDS turn-around and the stores.
+        // overlaps the LDS turn-around and the stores.  Old values and results bypass L2
+        // retention (non-temporal) for the same reason as above.
         float* Cw = static_cast<float*>(C) + int64_t(row0) * N + col0 + cb * 4;
         auto gaddr = [&](int p, int it) { return Cw + int64_t((p >> 1) * 32 + it * 4 + rsub) * N + (p & 1) * 64; };
         F4 old[3][8];
         auto fetch_old = [&](int p) {
 #pragma unroll
-            for (int it = 0; it < 8; ++it) old[p % 3][it] = *reinterpret_cast<const F4*>(gaddr(p, it));
+            for (int it = 0; it < 8; ++it) old[p % 3][it] = __builtin_nontemporal_load(reinterpret_cast<const F4*>(gaddr(p, it)));
         };
         if (kAccumulate) { fetch_old(0); fetch_old(1); }
 #pragma unroll
@@ -372,7 +395,7 @@ __device__ __forceinline__ void store_block(const f32x16 (&acc)[4][4], char* wld
                 const int m = it * 4 + rsub;
                 F4 v = *reinterpret_cast<const F4*>(wlds + m * 256 + ((cb ^ (m & 15)) << 4));
                 if (kAccumulate) v += old[p % 3][it];
-                *reinterpret_cast<F4*>(gaddr(p, it)) = v;
+                __builtin_nontemporal_store(v, reinterpret_cast<F4*>(gaddr(p, it)));
             }
         }
     }
