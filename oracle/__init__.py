@@ -227,3 +227,8 @@ def select_lowest(scores: Sequence[float], n_freeze: int) -> np.ndarray:
     for i in order[:n_freeze]:
         mask[i] = 1
     return mask
+
+
+# Metric-aware selection steps around the hot path (plain numpy; see selection.py).
+from .selection import (autofreeze_sqnorm, autofreeze_score, autofreeze_select,   # noqa: E402,F401
+                        perm32, perm32_inverse, reconcile_mask, pack_bits, unpack_bits)
