@@ -89,7 +89,9 @@ typedef enum {
     TF_KERNEL_DX_GENERIC = 2,   /* input-gradient GEMMs, fp32-FMA kernel      */
     TF_KERNEL_DW_GENERIC = 3,   /* weight-gradient GEMMs, fp32-FMA kernel     */
     TF_KERNEL_ADAMW = 4,        /* fused masked AdamW (+ stability EMAs)      */
-    TF_KERNEL_STABILITY = 5     /* stand-alone stability update               */
+    TF_KERNEL_STABILITY = 5,    /* stand-alone stability update               */
+    TF_KERNEL_AUTOFREEZE = 6,   /* norms of the cumulative updates            */
+    TF_KERNEL_RECONCILE = 7     /* every kernel of tf_reconcile_mask          */
 } tf_kernel_kind;
 int tf_profile_enable(tf_ctx* ctx, int enable);
 int tf_profile_collect(tf_ctx* ctx, int32_t capacity, int32_t* kinds, float* ms, int32_t* n_out);
@@ -207,6 +209,78 @@ int tf_stability_update(tf_ctx* ctx, void* hip_stream,
 int tf_stability_scores(const double* score_sums, int32_t n, double* scores);
 int tf_select_lowest(const double* scores, int32_t n, int32_t n_freeze, uint8_t* out_mask);
 int32_t tf_num_frozen(double r, int32_t n);
+
+/*
+ * AutoFreeze stability statistic (Sec. 2.3, "AutoFreeze"): the score of a layer
+ * at the K-th check is | ||D_{K-1}|| - ||D_K|| | / ||D_{K-1}|| with D_K the
+ * cumulative parameter update since the previous check, D_K = p_now - snapshot.
+ *
+ * tf_autofreeze_norms, per tensor i with tensor_freeze_mask[i] == 0 (or no mask):
+ *     sq_norms[i] = sum_j (p_master[i][j] - snapshot[i][j])^2      (fp64 sum)
+ *     snapshot[i] <- p_master[i]                  if update_snapshot != 0
+ * Tensors with mask 1 are skipped: sq_norms[i] and snapshot[i] stay as they are.
+ * Call it once per stability check; nothing is paid between checks.
+ *
+ *   numel            host, n_tensors
+ *   p_master_f32     host array of n_tensors DEVICE pointers, fp32, read only
+ *   snapshot_f32     host array of n_tensors DEVICE pointers, fp32, read (and written)
+ *   sq_norms         DEVICE, n_tensors doubles, 8-byte aligned; valid after the stream is synchronised
+ * Errors as for tf_masked_adamw.  Only enqueues.
+ *
+ * tf_autofreeze_scores (host only): scores[i] from sq_prev[i], sq_cur[i] (the
+ * squared norms of two consecutive checks); a zero previous norm gives 0 if
+ * the current one is zero too and +infinity otherwise.
+ *
+ * tf_autofreeze_select (host only): layers [0, n_already_frozen) are frozen.
+ * The threshold is the nearest-rank `percentile`-th percentile (P_Auto, Table
+ * exp_setup: 80) of the scores of the layers still trained; from the first
+ * trained layer on, layers are frozen while their score does not exceed it
+ * (a layer is frozen only if all layers before it are).  out_mask[i] = 1 frozen.
+ * TF_ERR_INVALID_ARG for NaN scores, percentile outside [0, 100] or
+ * n_already_frozen outside [0, n].
+ */
+int tf_autofreeze_norms(tf_ctx* ctx, void* hip_stream,
+                        int32_t n_tensors, const int64_t* numel,
+                        const void* const* p_master_f32, void* const* snapshot_f32,
+                        const uint8_t* tensor_freeze_mask, int update_snapshot,
+                        double* sq_norms);
+int tf_autofreeze_scores(const double* sq_prev, const double* sq_cur, int32_t n, double* scores);
+int tf_autofreeze_select(const double* scores, int32_t n, int32_t n_already_frozen,
+                         double percentile, uint8_t* out_mask);
+
+/*
+ * Metric-aware parameter selection of the hybrid variants (App. "Hybrid
+ * Variants Algorithm", Alg. 2): bring a base element mask over the N_s
+ * parameters of a stage to exactly n_freeze = floor(r N_s) ones.
+ *
+ *   ||base||_1 == n_freeze : the mask is left as it is
+ *   ||base||_1 <  n_freeze : n_freeze - ||base||_1 of its zeros, drawn uniformly, become ones
+ *   ||base||_1 >  n_freeze : ||base||_1 - n_freeze of its ones, drawn uniformly, become zeros
+ *
+ * The tensors are taken as one index space, concatenated in the order given.
+ * Drawing: candidates are ranked by the image of their stage-wide index under
+ * a permutation of [0, 2^32) keyed by `seed` (6-round Feistel network on 16-bit
+ * halves; round function: top 16 bits of ((half ^ key) + 1) * 0x9E3779B1 mod
+ * 2^32; round keys: the four 16-bit pieces of seed, low first, then bits 32..47
+ * and 48..63 of seed * 0xD1342543DE82EF95 mod 2^64) and the lowest ranks are
+ * drawn, so the result is a function of (mask, n_freeze, seed) alone.
+ *
+ *   numel            host, n_tensors; sum < 2^32
+ *   elem_bits        host array of n_tensors DEVICE pointers; bit j & 31 of word j >> 5
+ *                    is element j, 1 = frozen; updated in place; bits past numel are kept
+ *   n_freeze         0 <= n_freeze <= sum(numel)
+ *   stats            optional DEVICE, 3 x int64, 8-byte aligned: {||base||_1, case (0 kept,
+ *                    1 added, 2 removed), largest key drawn}; valid after the stream is synchronised
+ * Only enqueues (the rank search runs on the device).  Uses device memory owned by the
+ * context: calls on one context must not overlap.
+ * Errors: TF_ERR_INVALID_ARG, TF_ERR_SHAPE (numel <= 0, sum >= 2^32), TF_ERR_ALIGN
+ * (mask pointers not 4-byte, stats not 8-byte aligned), TF_ERR_HIP.
+ */
+int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
+                      int32_t n_tensors, const int64_t* numel,
+                      uint32_t* const* elem_bits,
+                      int64_t n_freeze, uint64_t seed,
+                      int64_t* stats);
 
 #ifdef __cplusplus
 }

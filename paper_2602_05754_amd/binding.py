@@ -21,9 +21,11 @@ EXPORTED_SYMBOLS = [
     "tf_stage_backward", "tf_masked_adamw", "tf_stability_update",
     "tf_stability_scores", "tf_select_lowest", "tf_num_frozen",
     "tf_profile_enable", "tf_profile_collect",
+    "tf_autofreeze_norms", "tf_autofreeze_scores", "tf_autofreeze_select", "tf_reconcile_mask",
 ]
 
-KERNEL_KINDS = {0: "dx_mfma", 1: "dw_mfma", 2: "dx_generic", 3: "dw_generic", 4: "adamw", 5: "stability"}
+KERNEL_KINDS = {0: "dx_mfma", 1: "dw_mfma", 2: "dx_generic", 3: "dw_generic", 4: "adamw", 5: "stability",
+                6: "autofreeze", 7: "reconcile"}
 
 
 class TfError(RuntimeError):
@@ -80,6 +82,14 @@ def load_library():
     lib.tf_profile_enable.argtypes = [vp, ctypes.c_int]
     lib.tf_profile_collect.restype = ctypes.c_int
     lib.tf_profile_collect.argtypes = [vp, i32, vp, vp, vp]
+    lib.tf_autofreeze_norms.restype = ctypes.c_int
+    lib.tf_autofreeze_norms.argtypes = [vp, vp, i32, vp, vp, vp, vp, ctypes.c_int, vp]
+    lib.tf_autofreeze_scores.restype = ctypes.c_int
+    lib.tf_autofreeze_scores.argtypes = [vp, vp, i32, vp]
+    lib.tf_autofreeze_select.restype = ctypes.c_int
+    lib.tf_autofreeze_select.argtypes = [vp, i32, i32, f64, vp]
+    lib.tf_reconcile_mask.restype = ctypes.c_int
+    lib.tf_reconcile_mask.argtypes = [vp, vp, i32, vp, vp, i64, ctypes.c_uint64, vp]
     _lib = lib
     return lib
 
@@ -326,3 +336,62 @@ def tf_select_lowest(scores, n_freeze: int) -> np.ndarray:
 
 def tf_num_frozen(r: float, n: int) -> int:
     return int(load_library().tf_num_frozen(float(r), int(n)))
+
+
+def tf_autofreeze_norms(ctx, numel: Sequence[int], p_master, snapshot, sq_norms,
+                        tensor_freeze_mask=None, update_snapshot: bool = True, stream=None) -> None:
+    """sq_norms[i] = sum((p_master[i] - snapshot[i])^2); snapshot <- p_master on request.  See include/tf.h."""
+    lib = load_library()
+    n = len(numel)
+    ne, ne_p = _host(numel, np.int64, n)
+    fm, fm_p = _host(tensor_freeze_mask, np.uint8, n)
+    for i in range(n):
+        if fm is not None and fm[i]:
+            continue
+        for name, seq in (("p_master", p_master), ("snapshot", snapshot)):
+            if seq is not None:
+                _check_numel(seq[i], int(ne[i]), TF_F32, f"{name}[{i}]")
+    keep = [_ptr_array(s, n) for s in (p_master, snapshot)]
+    rc = lib.tf_autofreeze_norms(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
+                                 n, ne_p, keep[0][1], keep[1][1], fm_p, int(bool(update_snapshot)), _dptr(sq_norms))
+    _raise(ctx, rc, "tf_autofreeze_norms")
+
+
+def tf_autofreeze_scores(sq_prev, sq_cur) -> np.ndarray:
+    """Host: | ||D_prev|| - ||D_cur|| | / ||D_prev|| per layer from squared norms."""
+    lib = load_library()
+    a = np.ascontiguousarray(np.asarray(sq_prev, dtype=np.float64).reshape(-1))
+    b = np.ascontiguousarray(np.asarray(sq_cur, dtype=np.float64).reshape(-1))
+    if a.size != b.size:
+        raise ValueError("sq_prev and sq_cur differ in length")
+    out = np.empty(max(a.size, 1), dtype=np.float64)
+    rc = lib.tf_autofreeze_scores(a.ctypes.data, b.ctypes.data, a.size, out.ctypes.data)
+    _raise(None, rc, "tf_autofreeze_scores")
+    return out[: a.size]
+
+
+def tf_autofreeze_select(scores, n_already_frozen: int, percentile: float) -> np.ndarray:
+    """Host: prefix freezing mask after one stability check (1 = frozen)."""
+    lib = load_library()
+    s = np.ascontiguousarray(np.asarray(scores, dtype=np.float64).reshape(-1))
+    out = np.zeros(max(s.size, 1), dtype=np.uint8)
+    rc = lib.tf_autofreeze_select(s.ctypes.data, s.size, int(n_already_frozen), float(percentile), out.ctypes.data)
+    _raise(None, rc, "tf_autofreeze_select")
+    return out[: s.size]
+
+
+def tf_reconcile_mask(ctx, numel: Sequence[int], elem_bits, n_freeze: int, seed: int, stats=None, stream=None) -> None:
+    """Bring the element masks (device uint32 words, updated in place) to exactly n_freeze ones.  See include/tf.h."""
+    lib = load_library()
+    n = len(numel)
+    ne, ne_p = _host(numel, np.int64, n)
+    for i in range(n):
+        x = elem_bits[i] if elem_bits is not None else None
+        if x is not None and not isinstance(x, int) and x.numel() * x.element_size() < ((int(ne[i]) + 31) // 32) * 4:
+            raise ValueError(f"elem_bits[{i}]: buffer smaller than {(int(ne[i]) + 31) // 32} mask words")
+    if stats is not None and not isinstance(stats, int) and stats.numel() * stats.element_size() < 24:
+        raise ValueError("stats: needs room for 3 int64 values")
+    keep = _ptr_array(elem_bits, n)
+    rc = lib.tf_reconcile_mask(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
+                               n, ne_p, keep[1], int(n_freeze), int(seed) & ((1 << 64) - 1), _dptr(stats))
+    _raise(ctx, rc, "tf_reconcile_mask")

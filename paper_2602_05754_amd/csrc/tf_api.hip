@@ -21,6 +21,7 @@ struct tf_ctx {
     bool profiling;
     std::vector<tf_prof_rec> recs;      // events recorded since the last tf_profile_collect
     std::vector<hipEvent_t> pool;       // events ready for reuse
+    tf::RcState* rc_state;              // device memory of tf_reconcile_mask (radix-select state)
 };
 
 namespace {
@@ -172,6 +173,11 @@ int tf_create(tf_ctx** out, int device_id) {
     ctx->device_id = device_id;
     ctx->last_hip_error = 0;
     ctx->profiling = false;
+    ctx->rc_state = nullptr;
+    if (hipMalloc(reinterpret_cast<void**>(&ctx->rc_state), tf::rc_state_bytes()) != hipSuccess) {
+        delete ctx;
+        return TF_ERR_WORKSPACE;
+    }
     *out = ctx;
     return TF_OK;
 }
@@ -180,6 +186,7 @@ int tf_destroy(tf_ctx* ctx) {
     if (!ctx) return TF_ERR_INVALID_ARG;
     for (tf_prof_rec& r : ctx->recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : ctx->pool) (void)hipEventDestroy(e);
+    if (ctx->rc_state) (void)hipFree(ctx->rc_state);
     delete ctx;
     return TF_OK;
 }
@@ -446,6 +453,155 @@ int32_t tf_num_frozen(double r, int32_t n) {
     const double x = std::ceil(r * double(n) - 1e-9);
     if (x >= double(n)) return n;
     return x < 0.0 ? 0 : int32_t(x);
+}
+
+int tf_autofreeze_norms(tf_ctx* ctx, void* hip_stream,
+                        int32_t n_tensors, const int64_t* numel,
+                        const void* const* p_master, void* const* snapshot,
+                        const uint8_t* tensor_freeze_mask, int update_snapshot,
+                        double* sq_norms) {
+    if (n_tensors < 0 || (update_snapshot != 0 && update_snapshot != 1)) return TF_ERR_INVALID_ARG;
+    if (n_tensors > 0) {
+        if (!numel || !p_master || !snapshot || !sq_norms) return TF_ERR_INVALID_ARG;
+        if (reinterpret_cast<uintptr_t>(sq_norms) & 7u) return TF_ERR_ALIGN;
+        for (int32_t i = 0; i < n_tensors; ++i) {
+            if (numel[i] <= 0 || numel[i] > (int64_t(1) << 40)) return TF_ERR_SHAPE;
+            if (tensor_freeze_mask && tensor_freeze_mask[i] > 1) return TF_ERR_INVALID_ARG;
+            if (tensor_freeze_mask && tensor_freeze_mask[i]) continue;
+            if (!p_master[i] || !snapshot[i]) return TF_ERR_INVALID_ARG;
+            if (!aligned16(p_master[i]) || !aligned16(snapshot[i])) return TF_ERR_ALIGN;
+        }
+    }
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    if (n_tensors == 0) return TF_OK;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int64_t epb = norm_elems_per_block();
+    NormBatch batch;
+    int n = 0;
+    int64_t blocks = 0;
+    auto flush = [&]() -> hipError_t {
+        if (n == 0) return hipSuccess;
+        batch.total_blocks = int32_t(blocks);
+        ProfScope prof(ctx, stream, TF_KERNEL_AUTOFREEZE);
+        const hipError_t e = launch_autofreeze_norms(stream, batch, n, update_snapshot != 0);
+        n = 0; blocks = 0;
+        return e;
+    };
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (tensor_freeze_mask && tensor_freeze_mask[i]) continue;
+        const int64_t nb = (numel[i] + epb - 1) / epb;
+        if (n == kMaxTensorsPerLaunch || blocks + nb > 0x3fffffff) {
+            const hipError_t e = flush();
+            if (e != hipSuccess) return hip_fail(ctx, e);
+        }
+        NormTensor& t = batch.t[n];
+        t.p = static_cast<const float*>(p_master[i]);
+        t.snap = static_cast<float*>(snapshot[i]);
+        t.out = sq_norms + i;
+        t.numel = numel[i];
+        t.block_start = int32_t(blocks);
+        t.pad_ = 0;
+        blocks += nb;
+        ++n;
+    }
+    const hipError_t e = flush();
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return TF_OK;
+}
+
+int tf_autofreeze_scores(const double* sq_prev, const double* sq_cur, int32_t n, double* scores) {
+    if (n < 0 || (n > 0 && (!sq_prev || !sq_cur || !scores))) return TF_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i)
+        if (!(sq_prev[i] >= 0.0) || !(sq_cur[i] >= 0.0)) return TF_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i) {
+        const double a = std::sqrt(sq_prev[i]), b = std::sqrt(sq_cur[i]);
+        if (a == 0.0) scores[i] = b == 0.0 ? 0.0 : INFINITY;
+        else scores[i] = std::fabs(a - b) / a;
+    }
+    return TF_OK;
+}
+
+int tf_autofreeze_select(const double* scores, int32_t n, int32_t n_already_frozen,
+                         double percentile, uint8_t* out_mask) {
+    if (n < 0 || n_already_frozen < 0 || n_already_frozen > n) return TF_ERR_INVALID_ARG;
+    if (!(percentile >= 0.0 && percentile <= 100.0)) return TF_ERR_INVALID_ARG;
+    if (n > 0 && (!scores || !out_mask)) return TF_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i)
+        if (std::isnan(scores[i])) return TF_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < n; ++i) out_mask[i] = i < n_already_frozen ? 1 : 0;
+    const int32_t n_active = n - n_already_frozen;
+    if (n_active == 0) return TF_OK;
+    std::vector<double> active(scores + n_already_frozen, scores + n);
+    std::sort(active.begin(), active.end());
+    const int32_t rank = int32_t(std::ceil(percentile / 100.0 * double(n_active) - 1e-9));
+    if (rank <= 0) return TF_OK;
+    const double tau = active[std::min(rank, n_active) - 1];
+    for (int32_t l = n_already_frozen; l < n && scores[l] <= tau; ++l) out_mask[l] = 1;
+    return TF_OK;
+}
+
+int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
+                      int32_t n_tensors, const int64_t* numel,
+                      uint32_t* const* elem_bits,
+                      int64_t n_freeze, uint64_t seed,
+                      int64_t* stats) {
+    if (n_tensors < 0 || n_freeze < 0) return TF_ERR_INVALID_ARG;
+    if (n_tensors > 0 && (!numel || !elem_bits)) return TF_ERR_INVALID_ARG;
+    if (stats && (reinterpret_cast<uintptr_t>(stats) & 7u)) return TF_ERR_ALIGN;
+    int64_t total = 0;
+    for (int32_t i = 0; i < n_tensors; ++i) {
+        if (numel[i] <= 0) return TF_ERR_SHAPE;
+        total += numel[i];
+        if (total >= (int64_t(1) << 32)) return TF_ERR_SHAPE;
+        if (!elem_bits[i]) return TF_ERR_INVALID_ARG;
+        if (reinterpret_cast<uintptr_t>(elem_bits[i]) & 3u) return TF_ERR_ALIGN;
+    }
+    if (n_freeze > total) return TF_ERR_INVALID_ARG;
+    if (!ctx) return TF_ERR_INVALID_ARG;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    RcKeys keys;
+    const uint64_t s2 = seed * 0xD1342543DE82EF95ull;
+    for (int r = 0; r < 4; ++r) keys.k[r] = uint32_t((seed >> (16 * r)) & 0xffffu);
+    keys.k[4] = uint32_t((s2 >> 32) & 0xffffu);
+    keys.k[5] = uint32_t((s2 >> 48) & 0xffffu);
+
+    const int64_t epb = rc_elems_per_block();
+    std::vector<RcBatch> batches;
+    {
+        RcBatch b;
+        b.n_tensors = 0; b.total_blocks = 0;
+        int64_t goff = 0, blocks = 0;
+        for (int32_t i = 0; i < n_tensors; ++i) {
+            const int64_t nb = (numel[i] + epb - 1) / epb;
+            if (b.n_tensors == kMaxTensorsPerLaunch || blocks + nb > 0x3fffffff) {
+                b.total_blocks = int32_t(blocks);
+                batches.push_back(b);
+                b.n_tensors = 0; blocks = 0;
+            }
+            RcTensor& t = b.t[b.n_tensors++];
+            t.bits = elem_bits[i]; t.numel = numel[i]; t.goff = goff;
+            t.block_start = int32_t(blocks); t.pad_ = 0;
+            blocks += nb;
+            goff += numel[i];
+        }
+        if (b.n_tensors > 0) { b.total_blocks = int32_t(blocks); batches.push_back(b); }
+    }
+
+    ProfScope prof(ctx, stream, TF_KERNEL_RECONCILE);
+    RcState* st = ctx->rc_state;
+    hipError_t e = launch_rc_begin(stream, st);
+    for (RcBatch& b : batches) if (e == hipSuccess) e = launch_rc_count(stream, b, st);
+    if (e == hipSuccess) e = launch_rc_decide(stream, st, uint64_t(n_freeze), stats);
+    const int shifts[3] = {21, 10, 0}, widths[3] = {11, 11, 10};
+    for (int pass = 0; pass < 3; ++pass) {
+        for (RcBatch& b : batches) if (e == hipSuccess) e = launch_rc_hist(stream, b, st, keys, shifts[pass], widths[pass]);
+        if (e == hipSuccess) e = launch_rc_pick(stream, st, widths[pass], pass == 2, stats);
+    }
+    for (RcBatch& b : batches) if (e == hipSuccess) e = launch_rc_apply(stream, b, st, keys);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return TF_OK;
 }
 
 }  // extern "C"

@@ -84,6 +84,60 @@ struct AdamwParams {
     float ema_decay, one_minus_ema_decay;
 };
 
+// ---------------------------------------------------------------------------
+// AutoFreeze norms: out[i] = sum((p - snapshot)^2), snapshot <- p on request.
+// ---------------------------------------------------------------------------
+struct NormTensor {
+    const float* p;
+    float* snap;
+    double* out;
+    int64_t numel;
+    int32_t block_start;
+    int32_t pad_;
+};
+struct NormBatch {          // passed by value as the kernel argument
+    NormTensor t[kMaxTensorsPerLaunch];
+    int32_t n_tensors;
+    int32_t total_blocks;
+    int32_t update_snapshot;
+    int32_t pad_;
+};
+int64_t norm_elems_per_block();
+hipError_t launch_autofreeze_norms(hipStream_t stream, NormBatch& batch, int n_tensors, bool update_snapshot);
+
+// ---------------------------------------------------------------------------
+// Budget reconciliation of an element mask (radix select over permutation keys).
+// ---------------------------------------------------------------------------
+struct RcTensor {
+    uint32_t* bits;         // element mask, 1 = frozen, LSB first
+    int64_t numel;
+    int64_t goff;           // stage-wide index of element 0
+    int32_t block_start;
+    int32_t pad_;
+};
+struct RcBatch {            // passed by value as the kernel argument
+    RcTensor t[kMaxTensorsPerLaunch];
+    int32_t n_tensors;
+    int32_t total_blocks;
+};
+struct RcKeys { uint32_t k[6]; };      // round keys of the index permutation
+struct RcState {            // device memory owned by the context
+    uint32_t hist[2048];
+    unsigned long long count;           // ones in the base mask
+    unsigned long long need;            // rank still to be located
+    uint32_t mode;                      // 0 keep, 1 add zeros, 2 remove ones
+    uint32_t prefix, prefix_bits;       // leading key bits fixed so far
+    uint32_t pad_;
+};
+int64_t rc_elems_per_block();
+size_t rc_state_bytes();
+hipError_t launch_rc_begin(hipStream_t stream, RcState* st);
+hipError_t launch_rc_count(hipStream_t stream, RcBatch& batch, RcState* st);
+hipError_t launch_rc_decide(hipStream_t stream, RcState* st, uint64_t n_freeze, int64_t* stats);
+hipError_t launch_rc_hist(hipStream_t stream, RcBatch& batch, RcState* st, const RcKeys& keys, int shift, int nbits);
+hipError_t launch_rc_pick(hipStream_t stream, RcState* st, int nbits, bool last, int64_t* stats);
+hipError_t launch_rc_apply(hipStream_t stream, RcBatch& batch, RcState* st, const RcKeys& keys);
+
 int64_t ew_elems_per_block();
 hipError_t launch_adamw(hipStream_t stream, EwBatch& batch, int n_tensors,
                         const AdamwParams& hp, Dtype grad_dtype);

@@ -164,3 +164,42 @@ kernel_c:
     assert [(f, ins.split()[0]) for f, _, ins in scc_hazards(split_carry)] == [("kernel_a", "s_addc_u32")]
     assert scc_hazards(fine) == []
     assert [(f, ins.split()[0]) for f, _, ins in scc_hazards(branch_on_stale)] == [("kernel_c", "s_cbranch_scc1")]
+
+
+def test_autofreeze_host_rules_match_the_oracle():
+    rs = np.random.default_rng(5)
+    prev = np.array([4.0, 4.0, 1.0, 9.0, 0.0, 0.0, 2.5])
+    cur = np.array([4.0, 1.0, 4.0, 0.0, 0.0, 1.0, 7.1])
+    got = tf.tf_autofreeze_scores(prev, cur)
+    exp = [oracle.autofreeze_score(a, b) for a, b in zip(prev, cur)]
+    assert got.tolist() == exp
+    for L in range(0, 8):
+        for trial in range(6):
+            sc = rs.integers(0, 3, size=L).astype(float) if trial % 2 else rs.random(L)
+            for k0 in range(L + 1):
+                for P in (0.0, 33.0, 50.0, 80.0, 100.0):
+                    assert np.array_equal(tf.tf_autofreeze_select(sc, k0, P), oracle.autofreeze_select(sc, k0, P)), (sc, k0, P)
+    inf = np.array([0.1, np.inf, 0.2])
+    assert np.array_equal(tf.tf_autofreeze_select(inf, 0, 80.0), oracle.autofreeze_select(inf, 0, 80.0))
+    for bad in (lambda: tf.tf_autofreeze_select([0.1, float("nan")], 0, 80.0), lambda: tf.tf_autofreeze_select([0.1], 2, 80.0),
+                lambda: tf.tf_autofreeze_select([0.1], 0, 101.0), lambda: tf.tf_autofreeze_scores([-1.0], [1.0])):
+        with pytest.raises(tf.TfError):
+            bad()
+
+
+def test_selection_entry_points_validate_before_any_gpu_work():
+    A = 4096   # fake aligned "device pointers": validation fails before anything is dereferenced
+    INV, SHAPE, ALIGN = -1, -2, -4
+    assert _code(tf.tf_autofreeze_norms, None, [8], [A], [A], A) == INV                      # no context: checked last
+    assert _code(tf.tf_autofreeze_norms, None, [0], [A], [A], A) == SHAPE
+    assert _code(tf.tf_autofreeze_norms, None, [8], [A + 4], [A], A) == ALIGN
+    assert _code(tf.tf_autofreeze_norms, None, [8], [A], [A], A + 4) == ALIGN
+    assert _code(tf.tf_autofreeze_norms, None, [8], [A], [None], A) == INV
+    assert _code(tf.tf_autofreeze_norms, None, [8], [None], [None], A, tensor_freeze_mask=[1]) == INV   # skipped tensor: only the context is missing
+    assert _code(tf.tf_reconcile_mask, None, [64], [A], 10, 1) == INV
+    assert _code(tf.tf_reconcile_mask, None, [0], [A], 0, 1) == SHAPE
+    assert _code(tf.tf_reconcile_mask, None, [1 << 31, 1 << 31], [A, A], 0, 1) == SHAPE       # 2^32 elements: keys are 32 bits
+    assert _code(tf.tf_reconcile_mask, None, [64], [A + 2], 10, 1) == ALIGN
+    assert _code(tf.tf_reconcile_mask, None, [64], [A], 65, 1) == INV                         # budget above N_s
+    assert _code(tf.tf_reconcile_mask, None, [64], [A], -1, 1) == INV
+    assert _code(tf.tf_reconcile_mask, None, [64], [A], 10, 1, stats=A + 4) == ALIGN
