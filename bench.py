@@ -47,9 +47,10 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5],
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6],
                     help="config id: 2 = LLaMA-1B-shaped stage (the benchmark line); 3 = LLaMA-8B stage; "
-                         "4 = elementwise pass only, Bernoulli element masks; 5 = 8 microbatches with fp32 dW accumulation")
+                         "4 = elementwise pass only, Bernoulli element masks; 5 = 8 microbatches with fp32 dW accumulation; "
+                         "6 = selection steps on the 8B stage's tensors (AutoFreeze norms, Alg. 2 budget reconciliation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -187,12 +188,14 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n,
                           "GBps": 2 * n / dt / 1e9}), flush=True)
         return
-    cfg = wl.CONFIGS[args.workload]
+    cfg = wl.CONFIGS[3 if args.workload == 6 else args.workload]
     ctx = tf.Context(0)
     if args.workload == 4:
         return bench_elementwise(args, cfg, ctx, wl, tf, torch)
     if args.workload == 5:
         return bench_microbatches(args, cfg, ctx, wl, tf, torch)
+    if args.workload == 6:
+        return bench_selection(args, cfg, ctx, wl, tf, torch)
     st = Stage(cfg, wl, tf, torch)
     L, T, P = st.L, st.T, cfg.n_params
 
@@ -372,6 +375,43 @@ def bench_elementwise(args, cfg, ctx, wl, tf, torch):
                      "dense_equivalent_GBps": P * 44 / kms / 1e6, "pct_hbm_peak_dense_equivalent": P * 44 / kms / 1e6 / 80.0})
         log(f"cfg4 r={r}: {kms:.3f} ms, algorithmic {rows[-1]['algorithmic_GBps']:.0f} GB/s, dense-equivalent {rows[-1]['dense_equivalent_GBps']:.0f} GB/s")
     print(json.dumps({"workload": "cfg4 llama8b-elementwise, 56 tensors, 1744830464 elements", "rows": rows}), flush=True)
+
+
+def bench_selection(args, cfg, ctx, wl, tf, torch):
+    """The selection steps beside the hot path at the 8B stage's size (56 tensors, 1.74e9 elements):
+    the AutoFreeze norm pass (12 B per element: p and snapshot read, snapshot written) and the Alg. 2
+    budget reconciliation of Bernoulli(0.3) base masks to r = 0.5 (add) and r = 0.1 (remove)."""
+    sizes = [k * n for k, n in cfg.shapes]
+    L, P = len(sizes), sum(sizes)
+    g = torch.Generator(device="cuda").manual_seed(wl.SEED_BASE + 6)
+    p = [torch.randn(n, generator=g, device="cuda") * cfg.w_std for n in sizes]
+    snap = [x + torch.randn(x.numel(), generator=g, device="cuda") * 1e-4 for x in p]
+    norms = torch.zeros(L, dtype=torch.float64, device="cuda")
+    dt, prof = _timed(ctx, torch, lambda: tf.tf_autofreeze_norms(ctx, sizes, p, snap, norms), args.steps, args.warmup)
+    kms = sum(t for k, t in prof if k == "autofreeze") / args.steps
+    out = {"workload": f"selection steps, {L} tensors, {P} elements",
+           "autofreeze_norms": {"ms_kernels": kms, "GBps": P * 12 / kms / 1e6, "pct_hbm_peak": P * 12 / kms / 1e6 / 80.0,
+                                "bytes_per_element": 12}}
+    log(f"autofreeze norms: {kms:.3f} ms, {out['autofreeze_norms']['GBps']:.0f} GB/s")
+    del snap
+    base = [(torch.rand((n + 31) // 32 * 32, generator=g, device="cuda") < 0.3).view(-1, 32).to(torch.int64)
+            .mul_(2 ** torch.arange(32, device="cuda", dtype=torch.int64)).sum(1).to(torch.int32) for n in sizes]
+    stats = torch.zeros(3, dtype=torch.int64, device="cuda")
+    rows = []
+    for r in (0.5, 0.1):
+        work = [b.clone() for b in base]
+        def fn():
+            for w, b in zip(work, base):
+                w.copy_(b)
+            tf.tf_reconcile_mask(ctx, sizes, work, int(r * P), 20260205754, stats=stats)
+        dt, prof = _timed(ctx, torch, fn, max(args.steps // 4, 3), 1)
+        kms = float(np.mean([t for k, t in prof if k == "reconcile"]))
+        st = stats.cpu().numpy()
+        rows.append({"r": r, "n_freeze": int(r * P), "base_ones": int(st[0]), "case": int(st[1]), "ms": kms,
+                     "Gelements_per_s": P / kms / 1e6})
+        log(f"reconcile r={r}: {kms:.3f} ms ({rows[-1]['Gelements_per_s']:.1f} G elements/s), case {int(st[1])}")
+    out["reconcile"] = rows
+    print(json.dumps(out), flush=True)
 
 
 def bench_microbatches(args, cfg, ctx, wl, tf, torch):

@@ -207,3 +207,56 @@ def test_llama8b_elementwise_pass_with_bernoulli_masks(ctx):
                 assert torch.equal(a[fz], b[fz]), f"step {step} tensor {l} {k}: frozen elements changed"
             se, sa = oracle.score_sums(h[l]["E"], h[l]["A"])
             assert np.isclose(got_sums[l, 0], se, rtol=1e-5) and np.isclose(got_sums[l, 1], sa, rtol=1e-5)
+
+
+def test_llama8b_stage_selection_steps_at_full_size(ctx):
+    """AutoFreeze norms and the Alg. 2 reconciliation over all 56 tensors of the 8B stage
+    (1.74e9 elements).  Inputs are drawn on the device (the host could not draw them in
+    reasonable time); the oracle checks whole tensors where affordable and properties plus
+    sampled elements elsewhere."""
+    cfg = wl.CONFIGS[3]
+    sizes = [k * n for k, n in cfg.shapes]
+    L, P = len(sizes), sum(sizes)
+    g = torch.Generator(device="cuda").manual_seed(wl.SEED_BASE + 66)
+    # --- norms: oracle on the first block's seven tensors in full, the snapshots of all
+    p = [torch.randn(n, generator=g, device="cuda") * 0.02 for n in sizes]
+    snap = [x + torch.randn(x.numel(), generator=g, device="cuda") * 1e-4 for x in p]
+    host = [(p[i].cpu().numpy(), snap[i].cpu().numpy()) for i in range(7)]
+    norms = torch.zeros(L, dtype=torch.float64, device="cuda")
+    tf.tf_autofreeze_norms(ctx, sizes, p, snap, norms)
+    got = norms.cpu().numpy()
+    for i in range(7):
+        assert got[i] == pytest.approx(oracle.autofreeze_sqnorm(*host[i]), rel=1e-12), i
+    for i in range(L):
+        assert torch.equal(snap[i], p[i])                                   # snapshot renewed, bit for bit
+        assert got[i] == pytest.approx(sizes[i] * 1e-8, rel=0.01)           # E||d||^2 = n sigma^2
+    del snap, host
+    # --- reconciliation
+    base = [(torch.rand((n + 31) // 32 * 32, generator=g, device="cuda") < 0.3).view(-1, 32).to(torch.int64)
+            .mul_(2 ** torch.arange(32, device="cuda", dtype=torch.int64)).sum(1).to(torch.int32) for n in sizes]
+    base_host = [b.cpu().numpy().view("<u4") for b in base]
+    base_ones = sum(int(np.bitwise_count(w).sum()) for w in base_host)
+    offs = np.concatenate([[0], np.cumsum(sizes)])
+    rs = np.random.default_rng(12)
+    for r, seed in ((0.5, 424242), (0.1, 99)):
+        nf = int(r * P)
+        work = [b.clone() for b in base]
+        stats = torch.zeros(3, dtype=torch.int64, device="cuda")
+        tf.tf_reconcile_mask(ctx, sizes, work, nf, seed, stats=stats)
+        st = stats.cpu().numpy()
+        new_host = [w.cpu().numpy().view("<u4") for w in work]
+        assert st[0] == base_ones and st[1] == (1 if base_ones < nf else 2)
+        assert sum(int(np.bitwise_count(w).sum()) for w in new_host) == nf           # the budget, exactly
+        for b, w in zip(base_host, new_host):                                        # superset / subset of the base mask
+            assert np.array_equal(w & b, b) if st[1] == 1 else np.array_equal(w | b, b)
+        # sampled elements: drawn exactly when a candidate's key does not exceed the largest key drawn
+        for t in rs.integers(0, L, 40):
+            j = rs.integers(0, sizes[t], 2000)
+            key = oracle.perm32(offs[t] + j, seed).astype(np.int64)
+            was = (base_host[t][j >> 5] >> (j & 31).astype(np.uint32)) & 1
+            now = (new_host[t][j >> 5] >> (j & 31).astype(np.uint32)) & 1
+            if st[1] == 1:
+                expect = was | ((was == 0) & (key <= st[2]))
+            else:
+                expect = was & ~((was == 1) & (key <= st[2])).astype(was.dtype)
+            assert np.array_equal(now, expect), (r, t)
