@@ -26,7 +26,8 @@ constexpr int kThreads = 256;
 // ------------------------------------------------------------------------------------------
 // AutoFreeze norms
 // ------------------------------------------------------------------------------------------
-constexpr int kNormGroup = 4, kNormIters = 4;
+// 8 iterations of 16 bytes per array and thread measured 13 % faster than 4 (and 2 much slower)
+constexpr int kNormGroup = 4, kNormIters = 8;
 constexpr int64_t kNormElemsPerBlock = int64_t(kThreads) * kNormGroup * kNormIters;
 typedef float F4 __attribute__((ext_vector_type(4)));
 
@@ -58,14 +59,15 @@ __global__ __launch_bounds__(kThreads) void norm_kernel(NormBatch batch) {
     for (int it = 0; it < kNormIters; ++it) {
         const int64_t j = chunk + (int64_t(it) * kThreads + threadIdx.x) * kNormGroup;
         if (j + kNormGroup <= numel) {
-            const F4 p = *reinterpret_cast<const F4*>(T.p + j);
-            const F4 s = *reinterpret_cast<const F4*>(T.snap + j);
+            // streamed once: non-temporal accesses measured 5 % faster
+            const F4 p = __builtin_nontemporal_load(reinterpret_cast<const F4*>(T.p + j));
+            const F4 s = __builtin_nontemporal_load(reinterpret_cast<const F4*>(T.snap + j));
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const double d = double(p[e]) - double(s[e]);      // exact
                 acc += d * d;
             }
-            if (batch.update_snapshot) *reinterpret_cast<F4*>(T.snap + j) = p;
+            if (batch.update_snapshot) __builtin_nontemporal_store(p, reinterpret_cast<F4*>(T.snap + j));
         } else {
             for (int64_t q = j; q < numel; ++q) {                  // ragged tail
                 const double d = double(T.p[q]) - double(T.snap[q]);
