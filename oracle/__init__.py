@@ -122,6 +122,39 @@ def stage_backward(shapes: Sequence[tuple], T: int, W, X, dY, freeze_mask,
         raise RuntimeError("oracle_stage_backward failed")
 
 
+def stage_backward_blocks(shapes: Sequence[tuple], T: int, W, X, dY, freeze_mask, row_masks, block_rows: int,
+                          dX, dW, accumulate: bool = False) -> None:
+    """Stage backward with sub-tensor freezing: as stage_backward, but of an unfrozen
+    layer l with row_masks[l] given only the row blocks b with row_masks[l][b] == 0 get
+    dW_l[rows of b] (+)= X_l[:, rows of b]^T dY_l; rows of frozen blocks are neither read
+    nor written.  dX is always computed in full (Sec. 3.2.1)."""
+    L = len(shapes)
+    all_frozen = np.ones(L, dtype=np.uint8)
+    stage_backward(shapes, T, W, X, dY, all_frozen, dX, [None] * L)              # dX only
+    fm = np.asarray(freeze_mask, dtype=np.uint8) if freeze_mask is not None else np.zeros(L, np.uint8)
+    for l, (K, N) in enumerate(shapes):
+        if fm[l]:
+            continue
+        rm = None if row_masks is None else row_masks[l]
+        if rm is None:
+            rm = np.zeros(K // block_rows if K % block_rows == 0 else 1, dtype=np.uint8)
+            br = block_rows if K % block_rows == 0 else K
+        else:
+            br = block_rows
+            if K % br or len(rm) != K // br:
+                raise ValueError("row mask does not match the layer")
+        for b, frozen in enumerate(rm):
+            if frozen:
+                continue
+            rows = slice(b * br, (b + 1) * br)
+            Xs = np.ascontiguousarray(X[l][:, rows])
+            Ws = np.ascontiguousarray(W[l][rows])
+            dWs = np.ascontiguousarray(dW[l][rows])
+            scratch = np.zeros((T, br))
+            stage_backward([(br, N)], T, [Ws], [Xs], [dY[l]], [0], [scratch], [dWs], accumulate)
+            dW[l][rows] = dWs
+
+
 def sample_dx(dY, W, ts, ks) -> np.ndarray:
     """Single elements of the input gradient, one by one: dX[t, k] = sum_n dY[t, n] W[k, n]
     (Sec. 3.2.1, activation-gradient component).  dY [T, N] and W [K, N] may be float32 or
@@ -231,4 +264,5 @@ def select_lowest(scores: Sequence[float], n_freeze: int) -> np.ndarray:
 
 # Metric-aware selection steps around the hot path (plain numpy; see selection.py).
 from .selection import (autofreeze_sqnorm, autofreeze_score, autofreeze_select,   # noqa: E402,F401
-                        perm32, perm32_inverse, reconcile_mask, pack_bits, unpack_bits)
+                        perm32, perm32_inverse, reconcile_mask, pack_bits, unpack_bits,
+                        select_row_blocks, row_blocks_to_elem_mask)

@@ -162,3 +162,47 @@ def reconcile_mask(base_bits: Sequence[np.ndarray], numel: Sequence[int], n_free
         out.append(new[o:o + n].copy())
         o += n
     return out, count
+
+
+# ---------------------------------------------------------------------------
+# Sub-tensor freezing: the unit is a block of `block_rows` consecutive rows of
+# a weight tensor (rows = input features), so that the frozen fraction of the
+# parameters can follow the freeze ratio closely (Sec. 3.2.1: the parameter-
+# gradient time shrinks with the fraction of parameters frozen; Alg. 1: a
+# random subset with |I| = AFR |P_s| in expectation).
+# ---------------------------------------------------------------------------
+
+
+def select_row_blocks(shapes: Sequence[tuple], block_rows: int, r: float, seed: int):
+    """Seeded draw of row blocks whose parameters add up to at most floor(r P).
+
+    Units are numbered layer by layer, block by block.  They are visited in the
+    order of the keys perm32(unit, seed); a unit is frozen if it still fits into
+    what is left of the budget.  Returns (list of uint8 masks, one per layer, 1 =
+    frozen block; number of frozen parameters)."""
+    sizes, owner = [], []
+    for l, (K, N) in enumerate(shapes):
+        if K % block_rows:
+            raise ValueError("block_rows must divide K")
+        for b in range(K // block_rows):
+            sizes.append(block_rows * N)
+            owner.append((l, b))
+    P = int(sum(sizes))
+    budget = int(math.floor(r * P + 1e-9))
+    order = np.argsort(perm32(np.arange(len(sizes)), seed), kind="stable")
+    masks = [np.zeros(K // block_rows, dtype=np.uint8) for K, _ in shapes]
+    frozen = 0
+    for u in order:
+        if frozen + sizes[u] <= budget:
+            frozen += sizes[u]
+            l, b = owner[u]
+            masks[l][b] = 1
+    return masks, frozen
+
+
+def row_blocks_to_elem_mask(shape, block_rows: int, row_mask) -> np.ndarray:
+    """0/1 per element of a [K x N] tensor (row-major, flattened): 1 where the row's block is frozen."""
+    K, N = shape
+    rm = np.asarray(row_mask, dtype=np.uint8)
+    assert rm.shape == (K // block_rows,)
+    return np.repeat(rm, block_rows * N)

@@ -172,3 +172,76 @@ def test_bit_packing_round_trip():
         assert w.dtype == np.dtype("<u4") and w.size == (n + 31) // 32
         assert np.array_equal(oracle.unpack_bits(w, n), b)
         assert (int(w[0]) & 1) == int(b[0])            # LSB first
+
+
+# ------------------------------------------------------- sub-tensor freezing
+def test_row_block_draw_fills_the_budget_to_within_one_unit():
+    shapes = [(2048, 2048), (2048, 512), (2048, 512), (2048, 2048), (2048, 8192), (2048, 8192), (8192, 2048)] * 2
+    P = sum(k * n for k, n in shapes)
+    smallest = 256 * 512
+    prev = None
+    for r in (0.0, 0.1, 0.25, 0.5, 0.75, 0.9, 1.0):
+        masks, frozen = oracle.select_row_blocks(shapes, 256, r, seed=7)
+        budget = math.floor(r * P + 1e-9)
+        assert frozen == sum(int(m.sum()) * 256 * n for m, (k, n) in zip(masks, shapes))
+        assert frozen <= budget
+        untaken = [256 * n for m, (k, n) in zip(masks, shapes) for f in m if not f]
+        assert not untaken or budget - frozen < min(untaken)           # no unit left that would still fit
+        assert budget - frozen < 256 * 8192                            # hence within one (largest) unit
+        assert [len(m) for m in masks] == [k // 256 for k, _ in shapes]
+    assert oracle.select_row_blocks(shapes, 256, 1.0, 3)[1] == P and oracle.select_row_blocks(shapes, 256, 0.0, 3)[1] == 0
+    a, _ = oracle.select_row_blocks(shapes, 256, 0.5, 11)
+    b, _ = oracle.select_row_blocks(shapes, 256, 0.5, 11)
+    c, _ = oracle.select_row_blocks(shapes, 256, 0.5, 12)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    assert any(not np.array_equal(x, y) for x, y in zip(a, c))
+    assert smallest > 0
+
+
+def test_row_block_draw_treats_equal_units_alike():
+    shapes = [(1024, 64)] * 2                       # 32 equal units of 32 rows
+    hits = np.zeros(64)
+    trials = 3000
+    for seed in range(trials):
+        masks, frozen = oracle.select_row_blocks(shapes, 32, 0.25, seed * 7919 + 3)
+        assert frozen == 16 * 32 * 64               # equal units: the budget is met exactly
+        hits += np.concatenate(masks)
+    chi2 = float(((hits - trials / 4) ** 2).sum() / (trials * 0.25 * 0.75))
+    assert 30.0 < chi2 < 110.0, chi2                # 63 degrees of freedom
+
+
+def test_backward_with_row_blocks_equals_the_full_backward_on_unfrozen_rows():
+    rng = np.random.default_rng(5)
+    shapes, T, br = [(8, 6), (12, 5), (4, 7)], 9, 4
+    W = [rng.standard_normal(s) for s in shapes]
+    X = [rng.standard_normal((T, k)) for k, n in shapes]
+    dY = [rng.standard_normal((T, n)) for k, n in shapes]
+    full_dX = [np.zeros((T, k)) for k, n in shapes]
+    full_dW = [np.zeros(s) for s in shapes]
+    oracle.stage_backward(shapes, T, W, X, dY, [0, 0, 0], full_dX, full_dW)
+    assert all(np.allclose(a, x.T @ g, atol=1e-12) for a, x, g in zip(full_dW, X, dY))      # the textbook product
+    canary = [np.full(s, np.nan) for s in shapes]
+    for a in canary:
+        a.view(np.uint64)[...] = 0x7FF8000000000ABC                                          # NaN with a payload
+    row_masks = [np.array([1, 0], np.uint8), np.array([0, 1, 0], np.uint8), None]
+    dX = [np.zeros((T, k)) for k, n in shapes]
+    dW = [c.copy() for c in canary]
+    oracle.stage_backward_blocks(shapes, T, W, X, dY, [0, 0, 0], row_masks, br, dX, dW)
+    for l, (k, n) in enumerate(shapes):
+        assert np.array_equal(dX[l], full_dX[l])                                              # dX does not depend on the masks
+        rm = row_masks[l] if row_masks[l] is not None else np.zeros(k // br, np.uint8)
+        for b, f in enumerate(rm):
+            rows = slice(b * br, (b + 1) * br)
+            if f:
+                assert dW[l][rows].tobytes() == canary[l][rows].tobytes()                     # frozen rows: not a bit changed
+            else:
+                assert np.array_equal(dW[l][rows], full_dW[l][rows])
+    # accumulation adds onto what is there; a frozen tensor overrides its row mask
+    acc = [np.ones(s) for s in shapes]
+    oracle.stage_backward_blocks(shapes, T, W, X, dY, [0, 1, 0], row_masks, br, dX, acc, accumulate=True)
+    assert np.array_equal(acc[1], np.ones(shapes[1]))
+    assert np.allclose(acc[0][4:], 1.0 + full_dW[0][4:]) and np.array_equal(acc[0][:4], np.ones((4, 6)))
+    assert np.allclose(acc[2], 1.0 + full_dW[2])
+    # all blocks frozen == tensor frozen; element mask of a row mask
+    em = oracle.row_blocks_to_elem_mask((8, 6), 4, [1, 0])
+    assert em.tolist() == [1] * 24 + [0] * 24
