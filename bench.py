@@ -47,10 +47,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6],
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7],
                     help="config id: 2 = LLaMA-1B-shaped stage (the benchmark line); 3 = LLaMA-8B stage; "
                          "4 = elementwise pass only, Bernoulli element masks; 5 = 8 microbatches with fp32 dW accumulation; "
-                         "6 = selection steps on the 8B stage's tensors (AutoFreeze norms, Alg. 2 budget reconciliation)")
+                         "6 = selection steps on the 8B stage's tensors (AutoFreeze norms, Alg. 2 budget reconciliation); "
+                         "7 = the benchmark stage with sub-tensor freezing (256-row blocks drawn under the parameter budget r P)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -188,7 +189,7 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n,
                           "GBps": 2 * n / dt / 1e9}), flush=True)
         return
-    cfg = wl.CONFIGS[3 if args.workload == 6 else args.workload]
+    cfg = wl.CONFIGS[{6: 3, 7: 2}.get(args.workload, args.workload)]
     ctx = tf.Context(0)
     if args.workload == 4:
         return bench_elementwise(args, cfg, ctx, wl, tf, torch)
@@ -196,6 +197,8 @@ def main():
         return bench_microbatches(args, cfg, ctx, wl, tf, torch)
     if args.workload == 6:
         return bench_selection(args, cfg, ctx, wl, tf, torch)
+    if args.workload == 7:
+        return bench_row_blocks(args, cfg, ctx, wl, tf, torch)
     st = Stage(cfg, wl, tf, torch)
     L, T, P = st.L, st.T, cfg.n_params
 
@@ -375,6 +378,47 @@ def bench_elementwise(args, cfg, ctx, wl, tf, torch):
                      "dense_equivalent_GBps": P * 44 / kms / 1e6, "pct_hbm_peak_dense_equivalent": P * 44 / kms / 1e6 / 80.0})
         log(f"cfg4 r={r}: {kms:.3f} ms, algorithmic {rows[-1]['algorithmic_GBps']:.0f} GB/s, dense-equivalent {rows[-1]['dense_equivalent_GBps']:.0f} GB/s")
     print(json.dumps({"workload": "cfg4 llama8b-elementwise, 56 tensors, 1744830464 elements", "rows": rows}), flush=True)
+
+
+def bench_row_blocks(args, cfg, ctx, wl, tf, torch):
+    """The benchmark stage (cfg 2) with sub-tensor freezing: 256-row blocks of the weight tensors are
+    drawn under the budget floor(r P) (tf_select_row_blocks), the backward skips their dW rows
+    (tf_stage_backward_blocks) and the optimizer skips their elements (element masks made by
+    tf_row_blocks_to_bits).  The frozen parameter fraction phi then equals r to within one block."""
+    st = Stage(cfg, wl, tf, torch)
+    L, T, P = st.L, st.T, cfg.n_params
+    bits = [torch.zeros((n + 31) // 32, dtype=torch.int32, device="cuda") for n in st.sizes]
+    hp = st.hp
+    rows = []
+    for r in (0.0, 0.1, 0.25, 0.5, 0.75, 0.9, 1.0):
+        masks, frozen = tf.tf_select_row_blocks(st.shapes, 256, r, 20260205754)
+        phi = frozen / P
+        tf.tf_row_blocks_to_bits(ctx, st.shapes, masks, 256, bits)
+        tmask = np.array([int(m.all()) for m in masks], dtype=np.uint8)        # wholly frozen tensors need no optimizer blocks
+        def step():
+            tf.tf_stage_backward_blocks(ctx, st.shapes, T, tf.TF_BF16, st.W, st.X, st.dY, None, masks, 256,
+                                        st.dX, st.dW, tf.TF_BF16)
+            tf.tf_masked_adamw(ctx, st.sizes, st.p, st.m, st.v, st.dW, tf.TF_BF16, st.steps, hp["lr"], hp["beta1"],
+                               hp["beta2"], hp["eps"], hp["weight_decay"], p_lowp=st.W, tensor_freeze_mask=tmask,
+                               elem_freeze_bits=bits, ema=st.E, ema_abs=st.A, ema_decay=st.decay)
+        dt, prof = _timed(ctx, torch, step, args.steps, 2)
+        k = {}
+        for name, ms in prof:
+            k.setdefault(name, []).append(ms)
+        per = {n: float(np.sum(v)) / args.steps for n, v in k.items()}
+        launches = {n: len(v) / args.steps for n, v in k.items()}
+        bwd = sum(v for n, v in per.items() if n.startswith("d"))
+        rows.append({"r": r, "phi": phi, "frozen_blocks": int(sum(int(m.sum()) for m in masks)), "ms_per_step": dt * 1e3,
+                     "backward_ms": bwd, "backward_tflops": 2.0 * T * P * (2.0 - phi) / bwd / 1e9,
+                     "dw_ms": per.get("dw_mfma", 0.0), "dw_launches": launches.get("dw_mfma", 0.0),
+                     "adamw_ms": per.get("adamw", 0.0),
+                     "adamw_algorithmic_GBps": (44.0 * (P - frozen) + P / 8.0) / per["adamw"] / 1e6 if per.get("adamw") else None})
+        log(f"row blocks r={r}: phi={phi:.4f} {dt * 1e3:.3f} ms/step, backward {bwd:.3f} ms "
+            f"(dW {rows[-1]['dw_ms']:.3f} ms in {rows[-1]['dw_launches']:.0f} launches), AdamW {rows[-1]['adamw_ms']:.3f} ms")
+    b0, b1 = rows[0]["backward_ms"], rows[-1]["backward_ms"]
+    for x in rows[1:-1]:
+        x["eta_backward"] = (b0 - x["backward_ms"]) / (x["phi"] * (b0 - b1))
+    print(json.dumps({"workload": f"cfg2 stage with 256-row-block freezing, L={L} tensors, P={P} params, T={T}", "rows": rows}), flush=True)
 
 
 def bench_selection(args, cfg, ctx, wl, tf, torch):

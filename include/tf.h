@@ -211,6 +211,56 @@ int tf_select_lowest(const double* scores, int32_t n, int32_t n_freeze, uint8_t*
 int32_t tf_num_frozen(double r, int32_t n);
 
 /*
+ * Sub-tensor freezing (Sec. 3.2.1: the parameter-gradient time shrinks with the
+ * fraction of parameters frozen; Alg. 1: a random subset I_i of the stage's
+ * parameters with |I_i| = AFR |P_s| in expectation).  The unit is a block of
+ * block_rows consecutive rows of a weight tensor W_l [K_l x N_l] (rows = input
+ * features), so that the frozen fraction of the parameters follows the freeze
+ * ratio to within one block instead of one tensor.
+ *
+ * tf_stage_backward_blocks: as tf_stage_backward, and in addition, for a layer l
+ * with freeze_mask[l] == 0 and row_block_mask[l] != NULL, only the row blocks b
+ * with row_block_mask[l][b] == 0 are computed:
+ *     dW_l[b*block_rows .. (b+1)*block_rows) (+)= X_l[:, those columns]^T * dY_l
+ * Rows of frozen blocks of dW_l are neither read nor written; dX is always
+ * computed in full.  Runs of unfrozen blocks are single GEMM problems; on the
+ * matrix cores when the run has a multiple of 256 rows (and N_l % 256 == 0,
+ * T % 64 == 0, bf16 inputs), otherwise on the fp32-FMA kernel.
+ *   row_block_mask   host array of n_layers HOST pointers (entries may be NULL: layer
+ *                    without row mask), each K_l / block_rows bytes, 1 = frozen; or NULL
+ *   block_rows       > 0; must divide K_l of every layer that has a row mask
+ * Errors as tf_stage_backward, plus TF_ERR_SHAPE when block_rows does not divide K_l.
+ *
+ * tf_select_row_blocks (host only): seeded draw of row blocks whose parameters add
+ * up to at most floor(r * P).  Units are numbered layer by layer, block by block;
+ * they are visited in the order of the keys perm32(unit number, seed) (the keyed
+ * permutation described at tf_reconcile_mask) and frozen if they still fit into
+ * what is left of the budget.  masks: sum_l K_l / block_rows bytes, layer after
+ * layer; frozen_params (optional): parameters frozen.
+ *
+ * tf_row_blocks_to_bits: element masks (the elem_freeze_bits of tf_masked_adamw)
+ * of row-block masks: bit j of elem_bits[l] = row_block_mask[l][(j / N_l) / block_rows],
+ * all zero for a layer without row mask.  elem_bits: host array of n_layers DEVICE
+ * pointers, ceil(K_l N_l / 32) words each, written.  block_rows * N_l must be a
+ * multiple of 32 for layers with a row mask (TF_ERR_SHAPE).  Only enqueues.
+ */
+int tf_stage_backward_blocks(tf_ctx* ctx, void* hip_stream,
+                             int32_t n_layers, const tf_shape* shapes,
+                             int64_t T, tf_dtype io_dtype,
+                             const void* const* W, const void* const* X, const void* const* dY,
+                             const uint8_t* freeze_mask,
+                             const uint8_t* const* row_block_mask, int32_t block_rows,
+                             void* const* dX,
+                             void* const* dW, tf_dtype dw_dtype,
+                             int accumulate);
+int tf_select_row_blocks(int32_t n_layers, const tf_shape* shapes, int32_t block_rows,
+                         double r, uint64_t seed, uint8_t* masks, int64_t* frozen_params);
+int tf_row_blocks_to_bits(tf_ctx* ctx, void* hip_stream,
+                          int32_t n_layers, const tf_shape* shapes,
+                          const uint8_t* const* row_block_mask, int32_t block_rows,
+                          uint32_t* const* elem_bits);
+
+/*
  * AutoFreeze stability statistic (Sec. 2.3, "AutoFreeze"): the score of a layer
  * at the K-th check is | ||D_{K-1}|| - ||D_K|| | / ||D_{K-1}|| with D_K the
  * cumulative parameter update since the previous check, D_K = p_now - snapshot.

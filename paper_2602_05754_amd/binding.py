@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = [
     "tf_stability_scores", "tf_select_lowest", "tf_num_frozen",
     "tf_profile_enable", "tf_profile_collect",
     "tf_autofreeze_norms", "tf_autofreeze_scores", "tf_autofreeze_select", "tf_reconcile_mask",
+    "tf_stage_backward_blocks", "tf_select_row_blocks", "tf_row_blocks_to_bits",
 ]
 
 KERNEL_KINDS = {0: "dx_mfma", 1: "dw_mfma", 2: "dx_generic", 3: "dw_generic", 4: "adamw", 5: "stability",
@@ -88,6 +89,13 @@ def load_library():
     lib.tf_autofreeze_scores.argtypes = [vp, vp, i32, vp]
     lib.tf_autofreeze_select.restype = ctypes.c_int
     lib.tf_autofreeze_select.argtypes = [vp, i32, i32, f64, vp]
+    lib.tf_stage_backward_blocks.restype = ctypes.c_int
+    lib.tf_stage_backward_blocks.argtypes = [vp, vp, i32, vp, i64, ctypes.c_int, vp, vp, vp, vp, vp, i32, vp, vp,
+                                             ctypes.c_int, ctypes.c_int]
+    lib.tf_select_row_blocks.restype = ctypes.c_int
+    lib.tf_select_row_blocks.argtypes = [i32, vp, i32, f64, ctypes.c_uint64, vp, vp]
+    lib.tf_row_blocks_to_bits.restype = ctypes.c_int
+    lib.tf_row_blocks_to_bits.argtypes = [vp, vp, i32, vp, vp, i32, vp]
     lib.tf_reconcile_mask.restype = ctypes.c_int
     lib.tf_reconcile_mask.argtypes = [vp, vp, i32, vp, vp, i64, ctypes.c_uint64, vp]
     _lib = lib
@@ -395,3 +403,87 @@ def tf_reconcile_mask(ctx, numel: Sequence[int], elem_bits, n_freeze: int, seed:
     rc = lib.tf_reconcile_mask(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
                                n, ne_p, keep[1], int(n_freeze), int(seed) & ((1 << 64) - 1), _dptr(stats))
     _raise(ctx, rc, "tf_reconcile_mask")
+
+
+def _host_mask_table(row_masks, shapes, block_rows):
+    """Host array of host pointers to per-layer uint8 row-block masks (NULL for None)."""
+    if row_masks is None:
+        return None, None
+    L = len(shapes)
+    if len(row_masks) != L:
+        raise ValueError(f"expected {L} row masks, got {len(row_masks)}")
+    keep = []
+    arr = (ctypes.c_void_p * max(L, 1))()
+    for l, m in enumerate(row_masks):
+        if m is None:
+            arr[l] = None
+            continue
+        a = np.ascontiguousarray(np.asarray(m, dtype=np.uint8).reshape(-1))
+        K = int(shapes[l][0])
+        if block_rows > 0 and K % block_rows == 0 and a.size != K // block_rows:
+            raise ValueError(f"row mask {l}: expected {K // block_rows} entries, got {a.size}")
+        keep.append(a)
+        arr[l] = a.ctypes.data
+    return (arr, keep), ctypes.cast(arr, ctypes.c_void_p)
+
+
+def tf_stage_backward_blocks(ctx, shapes: Sequence[tuple], T: int, io_dtype: int,
+                             W, X, dY, freeze_mask, row_block_mask, block_rows: int, dX, dW, dw_dtype: int,
+                             accumulate: bool = False, stream=None) -> None:
+    """Stage backward with sub-tensor freezing: of an unfrozen layer only the row blocks whose
+    row_block_mask entry is 0 get their part of dW.  See include/tf.h."""
+    lib = load_library()
+    L = len(shapes)
+    sh = np.ascontiguousarray(np.asarray(shapes, dtype=np.int64).reshape(L, 2))
+    fm, fm_p = _host(freeze_mask, np.uint8, L)
+    for l in range(L):
+        K, N = int(sh[l, 0]), int(sh[l, 1])
+        frozen = fm is not None and fm[l]
+        if W is not None: _check_numel(W[l], K * N, io_dtype, f"W[{l}]")
+        if dY is not None: _check_numel(dY[l], T * N, io_dtype, f"dY[{l}]")
+        if dX is not None: _check_numel(dX[l], T * K, io_dtype, f"dX[{l}]")
+        if not frozen:
+            if X is not None: _check_numel(X[l], T * K, io_dtype, f"X[{l}]")
+            if dW is not None: _check_numel(dW[l], K * N, dw_dtype, f"dW[{l}]")
+    keep = [_ptr_array(s, L) for s in (W, X, dY, dX, dW)]
+    rm_keep, rm_p = _host_mask_table(row_block_mask, [tuple(map(int, r)) for r in sh], int(block_rows))
+    rc = lib.tf_stage_backward_blocks(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
+                                      L, sh.ctypes.data, int(T), int(io_dtype),
+                                      keep[0][1], keep[1][1], keep[2][1], fm_p, rm_p, int(block_rows),
+                                      keep[3][1], keep[4][1], int(dw_dtype), 1 if accumulate else 0)
+    _raise(ctx, rc, "tf_stage_backward_blocks")
+
+
+def tf_select_row_blocks(shapes: Sequence[tuple], block_rows: int, r: float, seed: int):
+    """Host: seeded draw of row blocks under a parameter budget.  Returns (list of uint8 masks per layer, frozen params)."""
+    lib = load_library()
+    L = len(shapes)
+    sh = np.ascontiguousarray(np.asarray(shapes, dtype=np.int64).reshape(L, 2))
+    counts = [int(k) // int(block_rows) if block_rows > 0 and int(k) % int(block_rows) == 0 else 0 for k, _ in sh]
+    flat = np.zeros(max(sum(counts), 1), dtype=np.uint8)
+    frozen = ctypes.c_int64(0)
+    rc = lib.tf_select_row_blocks(L, sh.ctypes.data, int(block_rows), float(r), int(seed) & ((1 << 64) - 1),
+                                  flat.ctypes.data, ctypes.addressof(frozen))
+    _raise(None, rc, "tf_select_row_blocks")
+    out, o = [], 0
+    for c in counts:
+        out.append(flat[o:o + c].copy())
+        o += c
+    return out, int(frozen.value)
+
+
+def tf_row_blocks_to_bits(ctx, shapes: Sequence[tuple], row_block_mask, block_rows: int, elem_bits, stream=None) -> None:
+    """Element masks (device uint32 words, written) of row-block masks.  See include/tf.h."""
+    lib = load_library()
+    L = len(shapes)
+    sh = np.ascontiguousarray(np.asarray(shapes, dtype=np.int64).reshape(L, 2))
+    for l in range(L):
+        x = elem_bits[l] if elem_bits is not None else None
+        words = (int(sh[l, 0]) * int(sh[l, 1]) + 31) // 32
+        if x is not None and not isinstance(x, int) and x.numel() * x.element_size() < words * 4:
+            raise ValueError(f"elem_bits[{l}]: buffer smaller than {words} mask words")
+    keep = _ptr_array(elem_bits, L)
+    rm_keep, rm_p = _host_mask_table(row_block_mask, [tuple(map(int, r)) for r in sh], int(block_rows))
+    rc = lib.tf_row_blocks_to_bits(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
+                                   L, sh.ctypes.data, rm_p, int(block_rows), keep[1])
+    _raise(ctx, rc, "tf_row_blocks_to_bits")

@@ -64,9 +64,9 @@ __global__ __launch_bounds__(kThreads) void gemm_generic_kernel(GemmBatch batch)
             float a = 0.f, b = 0.f;
             if (gk < Kc) {
                 if (m0 + r < M)
-                    a = to_f32<TIn>(kContig ? A[int64_t(m0 + r) * Kc + gk] : A[int64_t(gk) * M + (m0 + r)]);
+                    a = to_f32<TIn>(kContig ? A[int64_t(m0 + r) * P.lda + gk] : A[int64_t(gk) * P.lda + (m0 + r)]);
                 if (n0 + r < N)
-                    b = to_f32<TIn>(kContig ? B[int64_t(n0 + r) * Kc + gk] : B[int64_t(gk) * N + (n0 + r)]);
+                    b = to_f32<TIn>(kContig ? B[int64_t(n0 + r) * P.ldb + gk] : B[int64_t(gk) * P.ldb + (n0 + r)]);
             }
             As[k][r] = a;
             Bs[k][r] = b;

@@ -216,7 +216,7 @@ template <bool kTN>
 __device__ __forceinline__ void stream_set_tile(StreamPos& c, Fill& f, const GemmBatch& batch, int vb) {
     const TilePos tp = locate_tile(batch, logical_tile(vb, batch.total_tiles), c.pi);
     const GemmProblem& P = batch.p[tp.pi];
-    const int64_t lda = kTN ? P.M : P.Kc, ldb = kTN ? P.N : P.Kc;
+    const int64_t lda = P.lda, ldb = P.ldb;
     f = make_fill<kTN>(static_cast<const uint16_t*>(P.A), static_cast<const uint16_t*>(P.B), lda, ldb, tp.m0, tp.n0);
     c.kstep_a = kTN ? int64_t(kBK) * lda * 2 : kBK * 2;
     c.kstep_b = kTN ? int64_t(kBK) * ldb * 2 : kBK * 2;
@@ -568,8 +568,9 @@ hipError_t launch_one(hipStream_t stream, const GemmBatch& batch) {
 
 int gemm_mfma_tile() { return kBM; }
 
-bool mfma_shape_ok(int64_t M, int64_t N, int64_t Kc) {
-    return M > 0 && N > 0 && Kc > 0 && M % kBM == 0 && N % kBN == 0 && Kc % kBK == 0;
+bool mfma_shape_ok(int64_t M, int64_t N, int64_t Kc, int64_t lda, int64_t ldb) {
+    // 16-byte direct loads: row pitches must keep every row 16-byte aligned
+    return M > 0 && N > 0 && Kc > 0 && M % kBM == 0 && N % kBN == 0 && Kc % kBK == 0 && lda % 8 == 0 && ldb % 8 == 0;
 }
 
 hipError_t launch_gemm_mfma_bf16(hipStream_t stream, GemmBatch& batch, int n_problems,

@@ -87,18 +87,6 @@ constexpr int kWordsPerThread = 4;
 constexpr int kWordsPerBlock = kThreads * kWordsPerThread;          // 1024 words = 32768 elements
 constexpr int kBins = 2048;
 
-__device__ __forceinline__ uint32_t perm32(uint32_t x, const RcKeys& k) {
-    uint32_t hi = x >> 16, lo = x & 0xffffu;
-#pragma unroll
-    for (int r = 0; r < 6; ++r) {
-        const uint32_t t = ((lo ^ k.k[r]) + 1u) * 0x9E3779B1u;
-        const uint32_t nh = lo;
-        lo = hi ^ (t >> 16);
-        hi = nh;
-    }
-    return (hi << 16) | lo;
-}
-
 struct RcWord {
     uint32_t* ptr;        // the word, or nullptr past the end of the tensor
     uint32_t valid;       // bits of the word that are elements of the tensor
@@ -219,7 +207,25 @@ __global__ __launch_bounds__(kThreads) void rc_apply_kernel(RcBatch batch, const
     }
 }
 
+// grid: (chunks, runs).  Run blockIdx.y, words [blockIdx.x * 4096 ...) four per thread and sweep.
+__global__ __launch_bounds__(kThreads) void fill_words_kernel(FillBatch batch) {
+    const FillRunDesc& R = batch.r[blockIdx.y];
+    for (int64_t w = int64_t(blockIdx.x) * kThreads + threadIdx.x; w < R.n_words; w += int64_t(gridDim.x) * kThreads)
+        R.dst[w] = R.value;
+}
+
 }  // namespace
+
+hipError_t launch_fill_words(hipStream_t stream, const FillBatch& batch) {
+    if (batch.n_runs == 0) return hipSuccess;
+    int64_t longest = 0;
+    for (int i = 0; i < batch.n_runs; ++i) longest = batch.r[i].n_words > longest ? batch.r[i].n_words : longest;
+    int64_t bx = (longest + kThreads * 4 - 1) / (kThreads * 4);
+    if (bx < 1) bx = 1;
+    if (bx > 4096) bx = 4096;
+    hipLaunchKernelGGL(fill_words_kernel, dim3(unsigned(bx), unsigned(batch.n_runs)), dim3(kThreads), 0, stream, batch);
+    return hipGetLastError();
+}
 
 int64_t norm_elems_per_block() { return kNormElemsPerBlock; }
 int64_t rc_elems_per_block() { return int64_t(kWordsPerBlock) * 32; }

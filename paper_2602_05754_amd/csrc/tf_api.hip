@@ -65,6 +65,7 @@ struct Planned {
     const void* B;
     void* C;
     int64_t M, N, Kc;
+    int64_t lda, ldb;       // row pitch of A, B in elements
 };
 
 // Launch `items` in batches of at most kMaxProblemsPerLaunch, MFMA-eligible ones on the
@@ -73,7 +74,7 @@ hipError_t launch_planned(tf_ctx* ctx, hipStream_t stream, std::vector<Planned>&
                           Dtype in_dtype, Dtype out_dtype, bool accumulate) {
     std::vector<Planned> fast, slow;
     for (const Planned& it : items) {
-        if (in_dtype == Dtype::BF16 && mfma_shape_ok(it.M, it.N, it.Kc)) fast.push_back(it);
+        if (in_dtype == Dtype::BF16 && mfma_shape_ok(it.M, it.N, it.Kc, it.lda, it.ldb) && aligned16(it.A) && aligned16(it.B) && aligned16(it.C)) fast.push_back(it);
         else slow.push_back(it);
     }
     // Longest contraction first: the tail of a launch is then made of the cheapest tiles.
@@ -96,6 +97,7 @@ hipError_t launch_planned(tf_ctx* ctx, hipStream_t stream, std::vector<Planned>&
                 GemmProblem& gp = batch.p[n];
                 gp.A = it.A; gp.B = it.B; gp.C = it.C;
                 gp.M = int32_t(it.M); gp.N = int32_t(it.N); gp.Kc = int32_t(it.Kc);
+                gp.lda = int32_t(it.lda); gp.ldb = int32_t(it.ldb);
                 gp.tile_start = int32_t(tiles);
                 tiles += nt;
                 ++n; ++i;
@@ -219,20 +221,22 @@ int tf_profile_collect(tf_ctx* ctx, int32_t capacity, int32_t* kinds, float* ms,
 
 int tf_last_hip_error(const tf_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
 
-int tf_stage_backward(tf_ctx* ctx, void* hip_stream,
-                      int32_t n_layers, const tf_shape* shapes,
-                      int64_t T, tf_dtype io_dtype,
-                      const void* const* W, const void* const* X, const void* const* dY,
-                      const uint8_t* freeze_mask,
-                      void* const* dX,
-                      void* const* dW, tf_dtype dw_dtype,
-                      int accumulate) {
+int tf_stage_backward_blocks(tf_ctx* ctx, void* hip_stream,
+                             int32_t n_layers, const tf_shape* shapes,
+                             int64_t T, tf_dtype io_dtype,
+                             const void* const* W, const void* const* X, const void* const* dY,
+                             const uint8_t* freeze_mask,
+                             const uint8_t* const* row_block_mask, int32_t block_rows,
+                             void* const* dX,
+                             void* const* dW, tf_dtype dw_dtype,
+                             int accumulate) {
     // ---- validation: no HIP call before this block has passed ----
     if (n_layers < 0) return TF_ERR_INVALID_ARG;
     if (!valid_dtype(io_dtype) || !valid_dtype(dw_dtype)) return TF_ERR_DTYPE;
     if (accumulate != 0 && accumulate != 1) return TF_ERR_INVALID_ARG;
     if (accumulate && dw_dtype != TF_F32) return TF_ERR_DTYPE;
     if (io_dtype == TF_F32 && dw_dtype != TF_F32) return TF_ERR_DTYPE;
+    if (row_block_mask && block_rows <= 0) return TF_ERR_INVALID_ARG;
     if (n_layers > 0) {
         if (!shapes || !W || !dY || !dX) return TF_ERR_INVALID_ARG;
         if (T <= 0 || T > 0x7fffffff) return TF_ERR_SHAPE;
@@ -250,6 +254,11 @@ int tf_stage_backward(tf_ctx* ctx, void* hip_stream,
             if (freeze_mask && freeze_mask[l]) continue;
             if (!X[l] || !dW[l]) return TF_ERR_INVALID_ARG;
             if (!aligned16(X[l]) || !aligned16(dW[l])) return TF_ERR_ALIGN;
+            if (row_block_mask && row_block_mask[l]) {
+                if (shapes[l].K % block_rows != 0) return TF_ERR_SHAPE;
+                for (int64_t b = 0; b < shapes[l].K / block_rows; ++b)
+                    if (row_block_mask[l][b] > 1) return TF_ERR_INVALID_ARG;
+            }
         }
     }
     if (!ctx) return TF_ERR_INVALID_ARG;
@@ -257,24 +266,54 @@ int tf_stage_backward(tf_ctx* ctx, void* hip_stream,
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Dtype in_dt = to_dtype(io_dtype);
+    const int64_t in_size = io_dtype == TF_BF16 ? 2 : 4, dw_size = dw_dtype == TF_BF16 ? 2 : 4;
 
-    // input gradients: every layer, whatever the mask says
+    // input gradients: every layer, whatever the masks say
     std::vector<Planned> plan;
     plan.reserve(n_layers);
     for (int32_t l = 0; l < n_layers; ++l)
-        plan.push_back(Planned{dY[l], W[l], dX[l], T, shapes[l].K, shapes[l].N});
+        plan.push_back(Planned{dY[l], W[l], dX[l], T, shapes[l].K, shapes[l].N, shapes[l].N, shapes[l].N});
     hipError_t e = launch_planned(ctx, stream, plan, Layout::kNT, in_dt, in_dt, false);
     if (e != hipSuccess) return hip_fail(ctx, e);
 
-    // weight gradients: unfrozen layers only; a frozen layer is simply not in the plan
+    // weight gradients: what is frozen - a layer, or a block of rows of one - is simply not
+    // in the plan.  Each run of unfrozen row blocks is one problem: columns [k0, k1) of X
+    // (pitch K_l) against dY give rows [k0, k1) of dW.
     plan.clear();
     for (int32_t l = 0; l < n_layers; ++l) {
         if (freeze_mask && freeze_mask[l]) continue;
-        plan.push_back(Planned{X[l], dY[l], dW[l], shapes[l].K, shapes[l].N, T});
+        const int64_t K = shapes[l].K, N = shapes[l].N;
+        const uint8_t* rm = row_block_mask ? row_block_mask[l] : nullptr;
+        if (!rm) {
+            plan.push_back(Planned{X[l], dY[l], dW[l], K, N, T, K, N});
+            continue;
+        }
+        const int64_t nb = K / block_rows;
+        for (int64_t b = 0; b < nb;) {
+            if (rm[b]) { ++b; continue; }
+            int64_t e1 = b;
+            while (e1 < nb && !rm[e1]) ++e1;
+            const int64_t k0 = b * block_rows, rows = (e1 - b) * block_rows;
+            plan.push_back(Planned{static_cast<const char*>(X[l]) + k0 * in_size, dY[l],
+                                   static_cast<char*>(dW[l]) + k0 * N * dw_size, rows, N, T, K, N});
+            b = e1;
+        }
     }
     e = launch_planned(ctx, stream, plan, Layout::kTN, in_dt, to_dtype(dw_dtype), accumulate != 0);
     if (e != hipSuccess) return hip_fail(ctx, e);
     return TF_OK;
+}
+
+int tf_stage_backward(tf_ctx* ctx, void* hip_stream,
+                      int32_t n_layers, const tf_shape* shapes,
+                      int64_t T, tf_dtype io_dtype,
+                      const void* const* W, const void* const* X, const void* const* dY,
+                      const uint8_t* freeze_mask,
+                      void* const* dX,
+                      void* const* dW, tf_dtype dw_dtype,
+                      int accumulate) {
+    return tf_stage_backward_blocks(ctx, hip_stream, n_layers, shapes, T, io_dtype, W, X, dY, freeze_mask,
+                                    nullptr, 0, dX, dW, dw_dtype, accumulate);
 }
 
 int tf_masked_adamw(tf_ctx* ctx, void* hip_stream,
@@ -561,11 +600,7 @@ int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
     if (!ctx) return TF_ERR_INVALID_ARG;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    RcKeys keys;
-    const uint64_t s2 = seed * 0xD1342543DE82EF95ull;
-    for (int r = 0; r < 4; ++r) keys.k[r] = uint32_t((seed >> (16 * r)) & 0xffffu);
-    keys.k[4] = uint32_t((s2 >> 32) & 0xffffu);
-    keys.k[5] = uint32_t((s2 >> 48) & 0xffffu);
+    const RcKeys keys = perm32_keys(seed);
 
     const int64_t epb = rc_elems_per_block();
     std::vector<RcBatch> batches;
@@ -600,6 +635,89 @@ int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
         if (e == hipSuccess) e = launch_rc_pick(stream, st, widths[pass], pass == 2, stats);
     }
     for (RcBatch& b : batches) if (e == hipSuccess) e = launch_rc_apply(stream, b, st, keys);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return TF_OK;
+}
+
+int tf_select_row_blocks(int32_t n_layers, const tf_shape* shapes, int32_t block_rows,
+                         double r, uint64_t seed, uint8_t* masks, int64_t* frozen_params) {
+    if (n_layers < 0 || block_rows <= 0 || !(r >= 0.0 && r <= 1.0)) return TF_ERR_INVALID_ARG;
+    if (n_layers > 0 && (!shapes || !masks)) return TF_ERR_INVALID_ARG;
+    struct Unit { uint32_t key; int64_t size; int64_t pos; };
+    std::vector<Unit> units;
+    const RcKeys keys = perm32_keys(seed);
+    int64_t total = 0;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        if (shapes[l].K <= 0 || shapes[l].N <= 0 || shapes[l].K % block_rows != 0) return TF_ERR_SHAPE;
+        for (int64_t b = 0; b < shapes[l].K / block_rows; ++b) {
+            if (units.size() >= 0xffffffffull) return TF_ERR_SHAPE;
+            const int64_t pos = int64_t(units.size());
+            units.push_back(Unit{perm32(uint32_t(pos), keys), int64_t(block_rows) * shapes[l].N, pos});
+            total += units.back().size;
+        }
+    }
+    const int64_t budget = int64_t(std::floor(r * double(total) + 1e-9));
+    std::sort(units.begin(), units.end(), [](const Unit& a, const Unit& b) { return a.key < b.key; });
+    for (size_t i = 0; i < units.size(); ++i) masks[i] = 0;
+    int64_t frozen = 0;
+    for (const Unit& u : units)
+        if (frozen + u.size <= budget) { frozen += u.size; masks[u.pos] = 1; }
+    if (frozen_params) *frozen_params = frozen;
+    return TF_OK;
+}
+
+int tf_row_blocks_to_bits(tf_ctx* ctx, void* hip_stream,
+                          int32_t n_layers, const tf_shape* shapes,
+                          const uint8_t* const* row_block_mask, int32_t block_rows,
+                          uint32_t* const* elem_bits) {
+    if (n_layers < 0 || block_rows <= 0) return TF_ERR_INVALID_ARG;
+    if (n_layers > 0 && (!shapes || !elem_bits)) return TF_ERR_INVALID_ARG;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        if (shapes[l].K <= 0 || shapes[l].N <= 0) return TF_ERR_SHAPE;
+        if (!elem_bits[l]) return TF_ERR_INVALID_ARG;
+        if (reinterpret_cast<uintptr_t>(elem_bits[l]) & 3u) return TF_ERR_ALIGN;
+        const uint8_t* rm = row_block_mask ? row_block_mask[l] : nullptr;
+        if (rm) {
+            if (shapes[l].K % block_rows != 0) return TF_ERR_SHAPE;
+            if ((int64_t(block_rows) * shapes[l].N) % 32 != 0) return TF_ERR_SHAPE;     // blocks must end on word boundaries
+            for (int64_t b = 0; b < shapes[l].K / block_rows; ++b)
+                if (rm[b] > 1) return TF_ERR_INVALID_ARG;
+        }
+    }
+    if (!ctx) return TF_ERR_INVALID_ARG;
+
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    FillBatch batch;
+    batch.n_runs = 0; batch.pad_ = 0;
+    auto push = [&](uint32_t* dst, int64_t n_words, uint32_t value) -> hipError_t {
+        if (n_words <= 0) return hipSuccess;
+        FillRunDesc& d = batch.r[batch.n_runs++];
+        d.dst = dst; d.n_words = n_words; d.value = value; d.pad_ = 0;
+        if (batch.n_runs == kMaxFillRuns) {
+            const hipError_t e = launch_fill_words(stream, batch);
+            batch.n_runs = 0;
+            return e;
+        }
+        return hipSuccess;
+    };
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const int64_t numel = shapes[l].K * shapes[l].N;
+        const uint8_t* rm = row_block_mask ? row_block_mask[l] : nullptr;
+        hipError_t e = hipSuccess;
+        if (!rm) {
+            e = push(elem_bits[l], (numel + 31) / 32, 0u);
+        } else {
+            const int64_t nb = shapes[l].K / block_rows, wpb = int64_t(block_rows) * shapes[l].N / 32;
+            for (int64_t b = 0; b < nb && e == hipSuccess;) {
+                int64_t e1 = b;
+                while (e1 < nb && rm[e1] == rm[b]) ++e1;
+                e = push(elem_bits[l] + b * wpb, (e1 - b) * wpb, rm[b] ? 0xffffffffu : 0u);
+                b = e1;
+            }
+        }
+        if (e != hipSuccess) return hip_fail(ctx, e);
+    }
+    const hipError_t e = launch_fill_words(stream, batch);
     if (e != hipSuccess) return hip_fail(ctx, e);
     return TF_OK;
 }

@@ -26,6 +26,7 @@ struct GemmProblem {
     void* C;
     int32_t M, N, Kc;
     int32_t tile_start;     // first tile index of this problem inside a launch
+    int32_t lda, ldb;       // row pitch of A and B in elements (kNT: >= Kc; kTN: >= M, >= N); C is dense
 };
 
 constexpr int kMaxProblemsPerLaunch = 64;
@@ -43,7 +44,7 @@ hipError_t launch_gemm_generic(hipStream_t stream, GemmBatch& batch, int n_probl
 
 // MFMA kernel for bf16 inputs.  Requires M % 256 == 0, N % 256 == 0, Kc % 64 == 0
 // for every problem in the batch (mfma_shape_ok).
-bool mfma_shape_ok(int64_t M, int64_t N, int64_t Kc);
+bool mfma_shape_ok(int64_t M, int64_t N, int64_t Kc, int64_t lda, int64_t ldb);
 hipError_t launch_gemm_mfma_bf16(hipStream_t stream, GemmBatch& batch, int n_problems,
                                  Layout layout, Dtype out_dtype, bool accumulate);
 int gemm_generic_tile();          // tile edge of the generic kernel (square)
@@ -121,6 +122,35 @@ struct RcBatch {            // passed by value as the kernel argument
     int32_t total_blocks;
 };
 struct RcKeys { uint32_t k[6]; };      // round keys of the index permutation
+
+// Keyed permutation of [0, 2^32): 6-round Feistel network on 16-bit halves; round function:
+// top 16 bits of ((half ^ key) + 1) * 0x9E3779B1 mod 2^32.
+__host__ __device__ inline uint32_t perm32(uint32_t x, const RcKeys& k) {
+    uint32_t hi = x >> 16, lo = x & 0xffffu;
+    for (int r = 0; r < 6; ++r) {
+        const uint32_t t = ((lo ^ k.k[r]) + 1u) * 0x9E3779B1u;
+        const uint32_t nh = lo;
+        lo = hi ^ (t >> 16);
+        hi = nh;
+    }
+    return (hi << 16) | lo;
+}
+// Round keys: the four 16-bit pieces of the seed, low first, then bits 32..47 and 48..63 of
+// seed * 0xD1342543DE82EF95 mod 2^64.
+inline RcKeys perm32_keys(uint64_t seed) {
+    RcKeys keys;
+    const uint64_t s2 = seed * 0xD1342543DE82EF95ull;
+    for (int r = 0; r < 4; ++r) keys.k[r] = uint32_t((seed >> (16 * r)) & 0xffffu);
+    keys.k[4] = uint32_t((s2 >> 32) & 0xffffu);
+    keys.k[5] = uint32_t((s2 >> 48) & 0xffffu);
+    return keys;
+}
+
+// Fill runs of 32-bit words with a constant (element masks of whole row blocks).
+struct FillRunDesc { uint32_t* dst; int64_t n_words; uint32_t value; uint32_t pad_; };
+constexpr int kMaxFillRuns = 128;
+struct FillBatch { FillRunDesc r[kMaxFillRuns]; int32_t n_runs; int32_t pad_; };
+hipError_t launch_fill_words(hipStream_t stream, const FillBatch& batch);
 struct RcState {            // device memory owned by the context
     uint32_t hist[2048];
     unsigned long long count;           // ones in the base mask

@@ -203,3 +203,35 @@ def test_selection_entry_points_validate_before_any_gpu_work():
     assert _code(tf.tf_reconcile_mask, None, [64], [A], 65, 1) == INV                         # budget above N_s
     assert _code(tf.tf_reconcile_mask, None, [64], [A], -1, 1) == INV
     assert _code(tf.tf_reconcile_mask, None, [64], [A], 10, 1, stats=A + 4) == ALIGN
+
+
+def test_row_block_draw_matches_the_oracle_rule():
+    shapes = [(2048, 2048), (2048, 512), (2048, 512), (2048, 2048), (2048, 8192), (2048, 8192), (8192, 2048)]
+    for br in (256, 512):
+        for r in (0.0, 0.1, 0.33, 0.5, 0.9, 1.0):
+            for seed in (0, 7, 0xFEEDFACECAFEBEEF):
+                got, frozen = tf.tf_select_row_blocks(shapes, br, r, seed)
+                exp, exp_frozen = oracle.select_row_blocks(shapes, br, r, seed)
+                assert frozen == exp_frozen and all(np.array_equal(a, b) for a, b in zip(got, exp)), (br, r, seed)
+    with pytest.raises(tf.TfError):
+        tf.tf_select_row_blocks([(100, 8)], 64, 0.5, 1)            # 64 does not divide 100
+    with pytest.raises(tf.TfError):
+        tf.tf_select_row_blocks([(128, 8)], 64, 1.5, 1)
+
+
+def test_row_block_entry_points_validate_before_any_gpu_work():
+    A = 4096
+    INV, SHAPE, ALIGN = -1, -2, -4
+    ok = dict(W=[A], X=[A], dY=[A], freeze_mask=[0], dX=[A], dW=[A])
+    call = lambda shapes, masks, br, **kw: _code(tf.tf_stage_backward_blocks, None, shapes, 8, tf.TF_F32,
+                                                 kw.get("W", ok["W"]), ok["X"], ok["dY"], ok["freeze_mask"], masks, br,
+                                                 ok["dX"], ok["dW"], tf.TF_F32)
+    assert call([(8, 8)], [[0, 1]], 4) == INV                       # everything fine but the context
+    assert call([(8, 8)], [[0, 1, 0]], 3) == SHAPE                  # 3 does not divide 8
+    assert call([(8, 8)], [[0, 2]], 4) == INV                       # mask values are 0 / 1
+    assert call([(8, 8)], [[0, 1]], 0) == INV
+    assert call([(8, 8)], [None], 4) == INV
+    assert call([(8, 8)], [[0, 1]], 4, W=[A + 2]) == ALIGN
+    assert _code(tf.tf_row_blocks_to_bits, None, [(8, 8)], [[0, 1]], 4, [A]) == INV
+    assert _code(tf.tf_row_blocks_to_bits, None, [(8, 6)], [[0, 1]], 4, [A]) == SHAPE     # 4 x 6 elements: not whole words
+    assert _code(tf.tf_row_blocks_to_bits, None, [(8, 8)], [[0, 1]], 4, [A + 1]) == ALIGN

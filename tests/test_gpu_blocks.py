@@ -1,0 +1,147 @@
+"""GPU parity of sub-tensor (row-block) freezing: tf_stage_backward_blocks and
+tf_row_blocks_to_bits against the oracle (Sec. 3.2.1; Alg. 1).  Bounds as for
+the stage backward: relative Frobenius 1e-5 (fp32) / 1e-2 (bf16) per output
+tensor over its unfrozen rows; rows of frozen blocks, frozen tensors and the
+optimizer state of frozen rows bit-identical; element masks bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_2602_05754_amd as tf
+from gpu_util import CODE, TDT, TOL, canary, dev, host64, raw_bytes, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = tf.Context(0)
+    yield c
+    c.close()
+
+
+def _inputs(rs, shapes, T, dtype):
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    W = [f32(rs.standard_normal(s) * 0.02) for s in shapes]
+    X = [f32(rs.standard_normal((T, k))) for k, n in shapes]
+    dY = [f32(rs.standard_normal((T, n)) * 1e-3) for k, n in shapes]
+    if dtype == "bf16":
+        W, X, dY = ([wl.round_to_bf16(a) for a in t] for t in (W, X, dY))
+    return W, X, dY
+
+
+def _case(ctx, shapes, T, dtype, block_rows, freeze_mask, row_masks, seed):
+    rs = np.random.default_rng(seed)
+    L = len(shapes)
+    W, X, dY = _inputs(rs, shapes, T, dtype)
+    f64 = lambda t: [np.asarray(a, dtype=np.float64) for a in t]
+    ref_dX = [np.zeros((T, k)) for k, n in shapes]
+    ref_dW = [np.zeros(s) for s in shapes]
+    oracle.stage_backward_blocks(shapes, T, f64(W), f64(X), f64(dY), freeze_mask, row_masks, block_rows, ref_dX, ref_dW)
+    gW, gX, gdY = ([dev(a, dtype) for a in t] for t in (W, X, dY))
+    gdX = [canary((T, k), TDT[dtype]) for k, n in shapes]
+    gdW = [canary(s, TDT[dtype]) for s in shapes]
+    before = [t.clone() for t in gdW]
+    tf.tf_stage_backward_blocks(ctx, shapes, T, CODE[dtype], gW, gX, gdY, freeze_mask, row_masks, block_rows, gdX, gdW, CODE[dtype])
+    torch.cuda.synchronize()
+    it = 4 if dtype == "f32" else 2
+    for l, (k, n) in enumerate(shapes):
+        assert rel_fro(host64(gdX[l]), ref_dX[l]) <= TOL[dtype], f"dX[{l}]"
+        if freeze_mask is not None and freeze_mask[l]:
+            assert raw_bytes(gdW[l]) == raw_bytes(before[l]), f"frozen dW[{l}] was touched"
+            continue
+        rm = row_masks[l] if row_masks is not None and row_masks[l] is not None else np.zeros(k // block_rows, np.uint8)
+        got = gdW[l]
+        for b, f in enumerate(rm):
+            rows = slice(b * block_rows, (b + 1) * block_rows)
+            if f:
+                assert raw_bytes(got[rows]) == raw_bytes(before[l][rows]), f"frozen rows {rows} of dW[{l}] were touched"
+            else:
+                assert rel_fro(host64(got[rows]), ref_dW[l][rows]) <= TOL[dtype], f"dW[{l}] rows {rows}"
+    return gW, gX, gdY, gdW
+
+
+def test_fp32_row_blocks_on_the_generic_kernel(ctx):
+    cfg = wl.CONFIGS[1]                                   # d=256, ffn=688: K in {256, 688}, 16-row blocks divide both
+    shapes = cfg.shapes
+    masks, frozen = oracle.select_row_blocks(shapes, 16, 0.5, seed=5)
+    P = sum(k * n for k, n in shapes)
+    assert abs(frozen / P - 0.5) < 0.01                   # the frozen fraction follows r to within one block
+    fm = np.zeros(len(shapes), np.uint8); fm[3] = 1       # a frozen tensor overrides its row mask
+    _case(ctx, shapes, 96, "f32", 16, fm, masks, seed=1)
+
+
+@pytest.mark.parametrize("block_rows", [256, 128])
+def test_bf16_row_blocks_on_the_matrix_cores(ctx, block_rows):
+    # runs of unfrozen blocks with a multiple of 256 rows take the MFMA kernel, the others the generic one
+    shapes = [(1024, 512), (512, 256), (2048, 256), (768, 768), (256, 512)]
+    rs = np.random.default_rng(block_rows)
+    masks = [(rs.random(k // block_rows) < 0.4).astype(np.uint8) for k, n in shapes]
+    masks[1] = None                                        # a layer without row mask
+    masks[4] = np.ones(256 // block_rows, np.uint8)        # every block frozen: nothing of dW is touched
+    masks[2][:] = 0; masks[2][1] = 1                       # a single hole
+    _case(ctx, shapes, 192, "bf16", block_rows, None, masks, seed=2)
+
+
+def test_row_block_element_masks_and_the_optimizer_that_follows(ctx):
+    shapes = [(512, 256), (256, 96), (128, 1000)]
+    br = 32
+    rs = np.random.default_rng(9)
+    masks = [(rs.random(k // br) < 0.5).astype(np.uint8) for k, n in shapes]
+    masks[1] = None
+    words = [torch.full(((k * n + 31) // 32,), 0x5A5A5A5A, dtype=torch.int32, device="cuda") for k, n in shapes]
+    tf.tf_row_blocks_to_bits(ctx, shapes, masks, br, words)
+    torch.cuda.synchronize()
+    elem = []
+    for l, (k, n) in enumerate(shapes):
+        exp = oracle.row_blocks_to_elem_mask((k, n), br, masks[l] if masks[l] is not None else np.zeros(k // br, np.uint8))
+        got = oracle.unpack_bits(words[l].cpu().numpy().view("<u4"), k * n)
+        assert np.array_equal(got, exp), l
+        elem.append(exp)
+    # one AdamW step under these masks: rows of frozen blocks keep every bit of p, m, v
+    numel = [k * n for k, n in shapes]
+    p0 = [np.ascontiguousarray(rs.standard_normal(n) * 0.02, dtype=np.float32) for n in numel]
+    g = [np.ascontiguousarray(rs.standard_normal(n) * 1e-3, dtype=np.float32) for n in numel]
+    dp = [torch.from_numpy(a.copy()).cuda() for a in p0]
+    dm = [torch.zeros(n, device="cuda") for n in numel]
+    dv = [torch.zeros(n, device="cuda") for n in numel]
+    dg = [torch.from_numpy(a).cuda() for a in g]
+    hp = {k: float(np.float32(v)) for k, v in dict(lr=1e-4, beta1=0.9, beta2=0.95, eps=1e-8, weight_decay=0.1).items()}
+    tf.tf_masked_adamw(ctx, numel, dp, dm, dv, dg, tf.TF_F32, [1] * 3, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"],
+                       hp["weight_decay"], elem_freeze_bits=words)
+    torch.cuda.synchronize()
+    for l in range(3):
+        p = np.asarray(p0[l], dtype=np.float64); m = np.zeros(numel[l]); v = np.zeros(numel[l])
+        oracle.masked_adamw(p, m, v, np.asarray(g[l], dtype=np.float64), step=1, elem_frozen=elem[l], **hp)
+        got = dp[l].cpu().numpy()
+        fr = elem[l].astype(bool)
+        assert np.array_equal(got[fr], p0[l][fr])                                   # frozen rows: bit-identical
+        assert np.all(dm[l].cpu().numpy()[fr] == 0) and np.all(dv[l].cpu().numpy()[fr] == 0)
+        assert rel_fro(got, p) <= 1e-5
+        assert (~fr).sum() == 0 or np.any(got[~fr] != p0[l][~fr])               # unfrozen rows did move
+
+
+def test_fp32_accumulation_with_a_different_row_mask_per_microbatch(ctx):
+    shapes = [(512, 256), (256, 256)]
+    T, br, M = 128, 256, 3
+    rs = np.random.default_rng(17)
+    masks = [[np.array([1, 0], np.uint8), np.array([0], np.uint8)],
+             [np.array([0, 0], np.uint8), np.array([1], np.uint8)],
+             [np.array([0, 1], np.uint8), np.array([0], np.uint8)]]
+    acc = [torch.zeros(s, device="cuda") for s in shapes]
+    ref = [np.zeros(s) for s in shapes]
+    W = None
+    for m in range(M):
+        Wm, X, dY = _inputs(rs, shapes, T, "bf16")
+        W = W or Wm
+        f64 = lambda t: [np.asarray(a, dtype=np.float64) for a in t]
+        dX = [np.zeros((T, k)) for k, n in shapes]
+        oracle.stage_backward_blocks(shapes, T, f64(W), f64(X), f64(dY), None, masks[m], br, dX, ref, accumulate=True)
+        gdX = [torch.empty((T, k), dtype=torch.bfloat16, device="cuda") for k, n in shapes]
+        tf.tf_stage_backward_blocks(ctx, shapes, T, tf.TF_BF16, [dev(a, "bf16") for a in W], [dev(a, "bf16") for a in X],
+                                    [dev(a, "bf16") for a in dY], None, masks[m], br, gdX, acc, tf.TF_F32, accumulate=True)
+    torch.cuda.synchronize()
+    for l in range(2):
+        assert rel_fro(host64(acc[l]), ref[l]) <= 1e-4, l

@@ -260,3 +260,37 @@ def test_llama8b_stage_selection_steps_at_full_size(ctx):
             else:
                 expect = was & ~((was == 1) & (key <= st[2])).astype(was.dtype)
             assert np.array_equal(now, expect), (r, t)
+
+
+def test_llama1b_stage_with_row_block_freezing_at_full_size(ctx):
+    """cfg 2 at full size with 256-row blocks drawn under the budget 0.5 P: the frozen parameter
+    fraction is 0.5 to within one block; sampled dW elements of unfrozen rows against one-by-one
+    oracle dots, rows of frozen blocks untouched, dX equal to the unmasked run's."""
+    cfg = wl.CONFIGS[2]
+    sh, T, L = cfg.shapes, cfg.T, cfg.n_layers
+    masks, frozen = tf.tf_select_row_blocks(sh, 256, 0.5, 77)
+    ref_masks, ref_frozen = oracle.select_row_blocks(sh, 256, 0.5, 77)
+    assert frozen == ref_frozen and all(np.array_equal(a, b) for a, b in zip(masks, ref_masks))
+    assert abs(frozen / cfg.n_params - 0.5) < 256 * 8192 / cfg.n_params
+    host = _gen(cfg)
+    gW = [dev(h[0], "bf16") for h in host]
+    gX = [dev(h[1], "bf16") for h in host]
+    gdY = [dev(h[2], "bf16") for h in host]
+    gdX = [canary((T, k), torch.bfloat16) for k, n in sh]
+    gdW = [canary((k, n), torch.bfloat16) for k, n in sh]
+    before = [t.clone() for t in gdW]
+    tf.tf_stage_backward_blocks(ctx, sh, T, tf.TF_BF16, gW, gX, gdY, None, masks, 256, gdX, gdW, tf.TF_BF16)
+    torch.cuda.synchronize()
+    rs = np.random.default_rng(31)
+    for l, (k, n) in enumerate(sh):
+        W, X, dY = host[l]
+        ts, ks = _tile_samples(rs, T, k, per_tile=1)
+        _check(_gather(gdX[l], ts, ks), oracle.sample_dx(dY, W, ts, ks), f"dX[{l}]")
+        kk, nn = _tile_samples(rs, k, n)
+        fr = masks[l][kk // 256].astype(bool)
+        got = _gather(gdW[l], kk, nn)
+        if (~fr).any():
+            _check(got[~fr], oracle.sample_dw(X, dY, kk[~fr], nn[~fr]), f"dW[{l}] unfrozen rows")
+        for b in np.flatnonzero(masks[l]):
+            rows = slice(b * 256, (b + 1) * 256)
+            assert torch.equal(gdW[l][rows].view(torch.int16), before[l][rows].view(torch.int16)), f"frozen rows of dW[{l}] touched"
