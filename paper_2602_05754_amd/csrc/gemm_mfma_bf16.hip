@@ -104,7 +104,13 @@ __device__ __forceinline__ TilePos locate_tile(const GemmBatch& batch, int lt, i
     const int first_m = (t / per_group) * kGroupM;
     const int gsz = min(tiles_m - first_m, kGroupM);
     t %= per_group;
-    return TilePos{pi, (first_m + t % gsz) * kBM, (t / gsz) * kBN};
+    int row = first_m + t % gsz;                      // tile row among the rows that exist
+    if (~P.row_bits != 0) {                           // the row-th set bit is the actual 256-row block
+        uint64_t b = P.row_bits;
+        for (int q = 0; q < row; ++q) b &= b - 1;
+        row = __ffsll(static_cast<long long>(b)) - 1;
+    }
+    return TilePos{pi, row * kBM, (t / gsz) * kBN};
 }
 
 // ---------------------------------------------------------------------------------------------

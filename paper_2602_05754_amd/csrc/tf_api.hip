@@ -66,6 +66,7 @@ struct Planned {
     void* C;
     int64_t M, N, Kc;
     int64_t lda, ldb;       // row pitch of A, B in elements
+    uint64_t row_bits;      // 256-row blocks that exist (MFMA kernel); all ones = dense
 };
 
 // Launch `items` in batches of at most kMaxProblemsPerLaunch, MFMA-eligible ones on the
@@ -75,6 +76,7 @@ hipError_t launch_planned(tf_ctx* ctx, hipStream_t stream, std::vector<Planned>&
     std::vector<Planned> fast, slow;
     for (const Planned& it : items) {
         if (in_dtype == Dtype::BF16 && mfma_shape_ok(it.M, it.N, it.Kc, it.lda, it.ldb) && aligned16(it.A) && aligned16(it.B) && aligned16(it.C)) fast.push_back(it);
+        else if (~it.row_bits != 0) return hipErrorInvalidValue;      // only the matrix-core kernel knows row bits
         else slow.push_back(it);
     }
     // Longest contraction first: the tail of a launch is then made of the cheapest tiles.
@@ -97,7 +99,7 @@ hipError_t launch_planned(tf_ctx* ctx, hipStream_t stream, std::vector<Planned>&
                 GemmProblem& gp = batch.p[n];
                 gp.A = it.A; gp.B = it.B; gp.C = it.C;
                 gp.M = int32_t(it.M); gp.N = int32_t(it.N); gp.Kc = int32_t(it.Kc);
-                gp.lda = int32_t(it.lda); gp.ldb = int32_t(it.ldb);
+                gp.lda = int32_t(it.lda); gp.ldb = int32_t(it.ldb); gp.row_bits = it.row_bits;
                 gp.tile_start = int32_t(tiles);
                 tiles += nt;
                 ++n; ++i;
@@ -272,30 +274,45 @@ int tf_stage_backward_blocks(tf_ctx* ctx, void* hip_stream,
     std::vector<Planned> plan;
     plan.reserve(n_layers);
     for (int32_t l = 0; l < n_layers; ++l)
-        plan.push_back(Planned{dY[l], W[l], dX[l], T, shapes[l].K, shapes[l].N, shapes[l].N, shapes[l].N});
+        plan.push_back(Planned{dY[l], W[l], dX[l], T, shapes[l].K, shapes[l].N, shapes[l].N, shapes[l].N, ~0ull});
     hipError_t e = launch_planned(ctx, stream, plan, Layout::kNT, in_dt, in_dt, false);
     if (e != hipSuccess) return hip_fail(ctx, e);
 
     // weight gradients: what is frozen - a layer, or a block of rows of one - is simply not
-    // in the plan.  Each run of unfrozen row blocks is one problem: columns [k0, k1) of X
-    // (pitch K_l) against dY give rows [k0, k1) of dW.
+    // in the plan.
     plan.clear();
     for (int32_t l = 0; l < n_layers; ++l) {
         if (freeze_mask && freeze_mask[l]) continue;
         const int64_t K = shapes[l].K, N = shapes[l].N;
         const uint8_t* rm = row_block_mask ? row_block_mask[l] : nullptr;
         if (!rm) {
-            plan.push_back(Planned{X[l], dY[l], dW[l], K, N, T, K, N});
+            plan.push_back(Planned{X[l], dY[l], dW[l], K, N, T, K, N, ~0ull});
             continue;
         }
         const int64_t nb = K / block_rows;
+        // Matrix-core path: one problem per tensor whose tile rows are the unfrozen 256-row
+        // blocks (a bit per block), so that any pattern of frozen blocks costs one problem.
+        const int64_t tile = gemm_mfma_tile();
+        if (in_dt == Dtype::BF16 && block_rows % tile == 0 && K / tile <= 64 &&
+            mfma_shape_ok(tile, N, T, K, N) && aligned16(X[l]) && aligned16(dY[l]) && aligned16(dW[l])) {
+            uint64_t bits = 0;
+            int64_t rows = 0;
+            const int64_t per = block_rows / tile;
+            for (int64_t b = 0; b < nb; ++b)
+                if (!rm[b])
+                    for (int64_t q = 0; q < per; ++q) { bits |= 1ull << (b * per + q); rows += tile; }
+            if (rows > 0) plan.push_back(Planned{X[l], dY[l], dW[l], rows, N, T, K, N, rows == K ? ~0ull : bits});
+            continue;
+        }
+        // Otherwise each run of unfrozen row blocks is one problem: columns [k0, k1) of X
+        // (pitch K_l) against dY give rows [k0, k1) of dW.
         for (int64_t b = 0; b < nb;) {
             if (rm[b]) { ++b; continue; }
             int64_t e1 = b;
             while (e1 < nb && !rm[e1]) ++e1;
             const int64_t k0 = b * block_rows, rows = (e1 - b) * block_rows;
             plan.push_back(Planned{static_cast<const char*>(X[l]) + k0 * in_size, dY[l],
-                                   static_cast<char*>(dW[l]) + k0 * N * dw_size, rows, N, T, K, N});
+                                   static_cast<char*>(dW[l]) + k0 * N * dw_size, rows, N, T, K, N, ~0ull});
             b = e1;
         }
     }

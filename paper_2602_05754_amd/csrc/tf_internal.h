@@ -27,6 +27,11 @@ struct GemmProblem {
     int32_t M, N, Kc;
     int32_t tile_start;     // first tile index of this problem inside a launch
     int32_t lda, ldb;       // row pitch of A and B in elements (kNT: >= Kc; kTN: >= M, >= N); C is dense
+    // MFMA kernel only: which 256-row blocks of the output (and of A) exist.  Bit b set = block b is
+    // computed; M counts the rows of the set bits only, tile row i of the problem is the i-th set
+    // bit.  All ones = dense.  This is how frozen row blocks of a weight gradient are skipped
+    // inside one grouped launch without touching their rows.
+    uint64_t row_bits;
 };
 
 constexpr int kMaxProblemsPerLaunch = 64;
