@@ -332,6 +332,49 @@ int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
                       int64_t n_freeze, uint64_t seed,
                       int64_t* stats);
 
+/*
+ * From measured action times to freeze ratios (Sec. 3.2), host only.
+ *
+ * Nodes: action (a, m, s) - a = 0 forward / 1 backward, microbatch m in [0, M),
+ * stage s in [0, S) - has id (a M + m) S + s; the source node is 2 M S, the
+ * destination 2 M S + 1 (both of duration 0).
+ *
+ * tf_pipeline_dag: the edges of one batch's schedule (App. "Edge Construction
+ * Rules"): source -> f(0,0) and b(M-1,0) -> destination; within a stage the
+ * microbatch order of forwards and of backwards and forward before its
+ * backward; forward s -> s+1 and backward s+1 -> s of the same microbatch; and
+ * the order in which a rank runs its actions - GPipe: all forwards, then all
+ * backwards; 1F1B: min(M, S-1-s) forwards, then one forward / one backward in
+ * turn, then the remaining backwards.  Writes min(capacity, *n_edges) pairs
+ * (from, to), sorted, without duplicates; *n_edges is the full count.
+ *
+ * tf_dag_start_times: P_i = max over predecessors j of (P_j + w_j), 0 for nodes
+ * without predecessor.  TF_ERR_INVALID_ARG for a graph with a cycle.
+ *
+ * tf_freeze_ratio_lp: the linear program of Sec. 3.2.2,
+ *     min  P_d - lambda * sum_i delta_i w_i
+ *     s.t. P_j >= P_i + w_i for every edge, w_min_i <= w_i <= w_max_i, P_source = 0,
+ *          for every stage: mean over its freezable nodes of r_i <= r_max,
+ * with delta_i = 1 / (w_max_i - w_min_i) (0 when the two are equal: not
+ * freezable) and r_i = delta_i (w_max_i - w_i).  w_min / w_max: 2 M S measured
+ * durations (all parameters frozen / none frozen).  Outputs (r required, the
+ * others optional): r and w per action, P per node (2 M S + 2, the longest-path
+ * start times at w), the batch time at w_max and at w.  The optimum's batch
+ * time is unique, its r need not be; the solver (dense two-phase simplex,
+ * Bland's rule) is deterministic.  S * M <= 4096.
+ *
+ * tf_actual_freeze_ratio: the progressive ratio of the freezing phase (Sec. 3.3):
+ * 0 for t <= T_m, min(r, r (t - T_m) / (T_f - T_m)) after.
+ */
+typedef enum { TF_SCHEDULE_GPIPE = 0, TF_SCHEDULE_1F1B = 1 } tf_schedule;
+int tf_pipeline_dag(int32_t n_stages, int32_t n_microbatches, tf_schedule schedule,
+                    int32_t capacity, int32_t* edges, int32_t* n_edges);
+int tf_dag_start_times(int32_t n_nodes, int32_t n_edges, const int32_t* edges, const double* w, double* P);
+int tf_freeze_ratio_lp(int32_t n_stages, int32_t n_microbatches, tf_schedule schedule,
+                       const double* w_min, const double* w_max, double r_max, double lambda,
+                       double* r, double* w, double* P, double* batch_time_max, double* batch_time);
+double tf_actual_freeze_ratio(double r, int64_t t, int64_t T_m, int64_t T_f);
+
 #ifdef __cplusplus
 }
 #endif

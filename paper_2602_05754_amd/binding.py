@@ -23,7 +23,11 @@ EXPORTED_SYMBOLS = [
     "tf_profile_enable", "tf_profile_collect",
     "tf_autofreeze_norms", "tf_autofreeze_scores", "tf_autofreeze_select", "tf_reconcile_mask",
     "tf_stage_backward_blocks", "tf_select_row_blocks", "tf_row_blocks_to_bits",
+    "tf_pipeline_dag", "tf_dag_start_times", "tf_freeze_ratio_lp", "tf_actual_freeze_ratio",
 ]
+
+TF_SCHEDULE_GPIPE = 0
+TF_SCHEDULE_1F1B = 1
 
 KERNEL_KINDS = {0: "dx_mfma", 1: "dw_mfma", 2: "dx_generic", 3: "dw_generic", 4: "adamw", 5: "stability",
                 6: "autofreeze", 7: "reconcile"}
@@ -96,6 +100,14 @@ def load_library():
     lib.tf_select_row_blocks.argtypes = [i32, vp, i32, f64, ctypes.c_uint64, vp, vp]
     lib.tf_row_blocks_to_bits.restype = ctypes.c_int
     lib.tf_row_blocks_to_bits.argtypes = [vp, vp, i32, vp, vp, i32, vp]
+    lib.tf_pipeline_dag.restype = ctypes.c_int
+    lib.tf_pipeline_dag.argtypes = [i32, i32, ctypes.c_int, i32, vp, vp]
+    lib.tf_dag_start_times.restype = ctypes.c_int
+    lib.tf_dag_start_times.argtypes = [i32, i32, vp, vp, vp]
+    lib.tf_freeze_ratio_lp.restype = ctypes.c_int
+    lib.tf_freeze_ratio_lp.argtypes = [i32, i32, ctypes.c_int, vp, vp, f64, f64, vp, vp, vp, vp, vp]
+    lib.tf_actual_freeze_ratio.restype = f64
+    lib.tf_actual_freeze_ratio.argtypes = [f64, i64, i64, i64]
     lib.tf_reconcile_mask.restype = ctypes.c_int
     lib.tf_reconcile_mask.argtypes = [vp, vp, i32, vp, vp, i64, ctypes.c_uint64, vp]
     _lib = lib
@@ -487,3 +499,49 @@ def tf_row_blocks_to_bits(ctx, shapes: Sequence[tuple], row_block_mask, block_ro
     rc = lib.tf_row_blocks_to_bits(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
                                    L, sh.ctypes.data, rm_p, int(block_rows), keep[1])
     _raise(ctx, rc, "tf_row_blocks_to_bits")
+
+
+def tf_pipeline_dag(n_stages: int, n_microbatches: int, schedule: int) -> np.ndarray:
+    """Host: edges (from, to) of one batch's schedule DAG, an [n_edges x 2] int32 array.  See include/tf.h."""
+    lib = load_library()
+    n = ctypes.c_int32(0)
+    rc = lib.tf_pipeline_dag(int(n_stages), int(n_microbatches), int(schedule), 0, None, ctypes.addressof(n))
+    _raise(None, rc, "tf_pipeline_dag")
+    edges = np.zeros((max(n.value, 1), 2), dtype=np.int32)
+    rc = lib.tf_pipeline_dag(int(n_stages), int(n_microbatches), int(schedule), n.value, edges.ctypes.data, ctypes.addressof(n))
+    _raise(None, rc, "tf_pipeline_dag")
+    return edges[: n.value]
+
+
+def tf_dag_start_times(n_nodes: int, edges, w) -> np.ndarray:
+    """Host: start times by longest path."""
+    lib = load_library()
+    e = np.ascontiguousarray(np.asarray(edges, dtype=np.int32).reshape(-1, 2))
+    wv = np.ascontiguousarray(np.asarray(w, dtype=np.float64).reshape(-1))
+    if wv.size != n_nodes:
+        raise ValueError("one duration per node")
+    P = np.zeros(max(n_nodes, 1), dtype=np.float64)
+    rc = lib.tf_dag_start_times(int(n_nodes), e.shape[0], e.ctypes.data, wv.ctypes.data, P.ctypes.data)
+    _raise(None, rc, "tf_dag_start_times")
+    return P[:n_nodes]
+
+
+def tf_freeze_ratio_lp(n_stages: int, n_microbatches: int, schedule: int, w_min, w_max, r_max: float, lam: float) -> dict:
+    """Host: expected freeze ratios from measured action times.  See include/tf.h."""
+    lib = load_library()
+    n_act = 2 * int(n_stages) * int(n_microbatches)
+    lo = np.ascontiguousarray(np.asarray(w_min, dtype=np.float64).reshape(-1))
+    hi = np.ascontiguousarray(np.asarray(w_max, dtype=np.float64).reshape(-1))
+    if lo.size != n_act or hi.size != n_act:
+        raise ValueError(f"expected {n_act} durations")
+    r = np.zeros(max(n_act, 1)); w = np.zeros(max(n_act, 1)); P = np.zeros(n_act + 2)
+    t_max, t_opt = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    rc = lib.tf_freeze_ratio_lp(int(n_stages), int(n_microbatches), int(schedule), lo.ctypes.data, hi.ctypes.data,
+                                float(r_max), float(lam), r.ctypes.data, w.ctypes.data, P.ctypes.data,
+                                ctypes.addressof(t_max), ctypes.addressof(t_opt))
+    _raise(None, rc, "tf_freeze_ratio_lp")
+    return {"r": r[:n_act], "w": w[:n_act], "P": P, "P_d_max": t_max.value, "P_d": t_opt.value}
+
+
+def tf_actual_freeze_ratio(r: float, t: int, T_m: int, T_f: int) -> float:
+    return float(load_library().tf_actual_freeze_ratio(float(r), int(t), int(T_m), int(T_f)))

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtf.so")
-SOURCES = ["tf_api.hip", "gemm_generic.hip", "gemm_mfma_bf16.hip", "elementwise.hip", "selection.hip"]
+SOURCES = ["tf_api.hip", "gemm_generic.hip", "gemm_mfma_bf16.hip", "elementwise.hip", "selection.hip", "schedule_lp.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

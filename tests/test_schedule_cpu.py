@@ -1,0 +1,98 @@
+"""The library's host-side schedule steps (pipeline DAG, start times, the
+freeze-ratio linear program, progressive ratio; Sec. 3.2, 3.3) against the
+oracle.  The LP's optimal batch time is unique and must agree; its ratios need
+not be unique, so the library's are checked for feasibility and for the same
+objective value."""
+import numpy as np
+import pytest
+
+import paper_2602_05754_amd as tf
+from oracle import schedule as sc
+
+CASES = [(1, 1, 0), (1, 3, 1), (2, 2, 0), (2, 2, 1), (3, 2, 1), (2, 5, 0), (4, 8, 0), (4, 8, 1), (8, 8, 1), (3, 7, 1)]
+
+
+@pytest.mark.parametrize("S,M,sched", CASES)
+def test_dag_and_start_times(S, M, sched):
+    got = tf.tf_pipeline_dag(S, M, sched)
+    exp = sc.pipeline_dag(S, M, sched)
+    assert [tuple(e) for e in got.tolist()] == exp                   # same edges, same (sorted) order
+    n = 2 * M * S + 2
+    rng = np.random.default_rng(S * 31 + M)
+    w = np.r_[rng.uniform(0.1, 3.0, n - 2), 0.0, 0.0]
+    assert np.allclose(tf.tf_dag_start_times(n, got, w), sc.start_times(n, exp, w), rtol=1e-13, atol=0)
+
+
+def test_start_times_reject_cycles_and_bad_input():
+    with pytest.raises(tf.TfError):
+        tf.tf_dag_start_times(3, [(0, 1), (1, 2), (2, 0)], [1.0, 1.0, 1.0])
+    with pytest.raises(tf.TfError):
+        tf.tf_dag_start_times(2, [(0, 5)], [1.0, 1.0])
+    with pytest.raises(tf.TfError):
+        tf.tf_dag_start_times(2, [(0, 1)], [1.0, -1.0])
+    with pytest.raises(tf.TfError):
+        tf.tf_pipeline_dag(0, 2, 0)
+    with pytest.raises(tf.TfError):
+        tf.tf_pipeline_dag(2, 2, 5)
+
+
+def _times(S, M, seed, frac=(0.4, 0.7)):
+    rng = np.random.default_rng(seed)
+    n_act = 2 * M * S
+    w_max = rng.uniform(1.0, 3.0, n_act)
+    w_min = w_max.copy()
+    for m in range(M):
+        for s in range(S):
+            i = sc.node_id(1, m, s, M, S)
+            w_min[i] = w_max[i] * rng.uniform(*frac)
+    return w_min, w_max
+
+
+@pytest.mark.parametrize("S,M,sched", [(2, 2, 0), (2, 2, 1), (3, 2, 1), (2, 4, 0), (4, 8, 0), (4, 8, 1), (4, 4, 1), (6, 8, 1)])
+def test_freeze_ratio_lp_against_the_oracle(S, M, sched):
+    lam = 1e-4
+    n_act = 2 * M * S
+    for seed, r_max in [(1, 0.8), (2, 0.5), (3, 1.0), (4, 0.0), (5, 0.3)]:
+        w_min, w_max = _times(S, M, seed * 100 + S * 10 + M)
+        got = tf.tf_freeze_ratio_lp(S, M, sched, w_min, w_max, r_max, lam)
+        ref = sc.freeze_ratio_lp(S, M, sched, w_min, w_max, r_max, lam)
+        assert got["P_d_max"] == pytest.approx(ref["P_d_max"], rel=1e-12)
+        assert got["P_d"] == pytest.approx(ref["P_d"], rel=1e-7)
+        # same objective: P_d - lam sum delta_i w_i
+        rng_ = w_max - w_min
+        delta = np.where(rng_ > 0, 1.0 / np.where(rng_ > 0, rng_, 1.0), 0.0)
+        obj = got["P_d"] - lam * float((delta * got["w"]).sum())
+        assert obj == pytest.approx(ref["objective"], rel=1e-7, abs=1e-9)
+        # feasibility of the library's own solution
+        r, w = got["r"], got["w"]
+        assert np.all(w >= w_min - 1e-9) and np.all(w <= w_max + 1e-9)
+        assert np.allclose(r, np.where(rng_ > 0, (w_max - w) * delta, 0.0), atol=1e-9)
+        assert np.all(r[: M * S] == 0.0)
+        for s in range(S):
+            assert np.mean([r[sc.node_id(1, m, s, M, S)] for m in range(M)]) <= r_max + 1e-7
+        n = n_act + 2
+        P = sc.start_times(n, sc.pipeline_dag(S, M, sched), np.r_[w, 0.0, 0.0])
+        assert np.allclose(got["P"], P, rtol=1e-12, atol=1e-12) and got["P_d"] == pytest.approx(P[-1], rel=1e-12)
+
+
+def test_lp_scale_invariance_and_degenerate_inputs():
+    S, M = 3, 4
+    w_min, w_max = _times(S, M, 9)
+    a = tf.tf_freeze_ratio_lp(S, M, 1, w_min, w_max, 0.8, 1e-4)
+    b = tf.tf_freeze_ratio_lp(S, M, 1, w_min * 1e3, w_max * 1e3, 0.8, 1e-4 * 1e3)      # milliseconds instead of seconds
+    assert b["P_d"] == pytest.approx(a["P_d"] * 1e3, rel=1e-9) and np.allclose(a["r"], b["r"], atol=1e-7)
+    # nothing freezable: the batch time is the longest path and every ratio is 0
+    c = tf.tf_freeze_ratio_lp(S, M, 0, w_max, w_max, 0.8, 1e-4)
+    assert c["P_d"] == pytest.approx(c["P_d_max"]) and np.all(c["r"] == 0)
+    for bad in (lambda: tf.tf_freeze_ratio_lp(S, M, 1, w_max, w_min, 0.8, 1e-4),       # min above max
+                lambda: tf.tf_freeze_ratio_lp(S, M, 1, w_min, w_max, 1.5, 1e-4),
+                lambda: tf.tf_freeze_ratio_lp(S, M, 1, w_min, w_max, 0.8, 2.0),
+                lambda: tf.tf_freeze_ratio_lp(S, M, 7, w_min, w_max, 0.8, 1e-4)):
+        with pytest.raises(tf.TfError):
+            bad()
+
+
+def test_progressive_ratio_matches_the_oracle():
+    for r in (0.0, 0.37, 0.8, 1.0):
+        for t in (0, 99, 100, 101, 150, 199, 200, 201, 10 ** 6):
+            assert tf.tf_actual_freeze_ratio(r, t, 100, 200) == pytest.approx(sc.actual_freeze_ratio(r, t, 100, 200), abs=1e-15)
