@@ -166,12 +166,24 @@ __global__ __launch_bounds__(kThreads) void rc_hist_kernel(RcBatch batch, RcStat
 }
 
 // Pick the bin in which the need-th smallest key lies; extend the prefix by its digit.
-__global__ void rc_pick_kernel(RcState* st, int nbits, int last, long long* stats) {
-    if (threadIdx.x != 0) return;
-    if (st->mode != 0) {
+// One block of 256 threads: each sums 8 neighbouring bins, thread 0 walks the 256 partial sums
+// and then the 8 bins of the one that holds the rank; all of them clear the histogram.
+__global__ __launch_bounds__(kThreads) void rc_pick_kernel(RcState* st, int nbits, int last, long long* stats) {
+    __shared__ unsigned long long part[kThreads];
+    constexpr int kPer = kBins / kThreads;
+    unsigned long long mine = 0;
+    for (int q = 0; q < kPer; ++q) mine += st->hist[threadIdx.x * kPer + q];
+    part[threadIdx.x] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0 && st->mode != 0) {
         const int bins = 1 << nbits;
         unsigned long long before = 0;
-        int b = 0;
+        int g = 0;
+        for (; g < kThreads - 1 && (g + 1) * kPer < bins; ++g) {
+            if (before + part[g] >= st->need) break;
+            before += part[g];
+        }
+        int b = g * kPer;
         for (; b < bins - 1; ++b) {
             const unsigned long long hb = st->hist[b];
             if (before + hb >= st->need) break;
@@ -180,9 +192,11 @@ __global__ void rc_pick_kernel(RcState* st, int nbits, int last, long long* stat
         st->need -= before;                      // rank inside the bin, >= 1
         st->prefix = (st->prefix << nbits) | uint32_t(b);
         st->prefix_bits += uint32_t(nbits);
+        if (last && stats) stats[2] = (long long)st->prefix;
     }
-    for (int i = 0; i < kBins; ++i) st->hist[i] = 0;
-    if (last && stats) stats[2] = st->mode ? (long long)st->prefix : 0;
+    if (threadIdx.x == 0 && st->mode == 0 && last && stats) stats[2] = 0;
+    __syncthreads();
+    for (int q = 0; q < kPer; ++q) st->hist[threadIdx.x * kPer + q] = 0;
 }
 
 // After the last digit the prefix is a full key: the need-th smallest.  Candidates with a key
@@ -260,7 +274,7 @@ hipError_t launch_rc_hist(hipStream_t stream, RcBatch& batch, RcState* st, const
     return hipGetLastError();
 }
 hipError_t launch_rc_pick(hipStream_t stream, RcState* st, int nbits, bool last, int64_t* stats) {
-    hipLaunchKernelGGL(rc_pick_kernel, dim3(1), dim3(64), 0, stream, st, nbits, last ? 1 : 0,
+    hipLaunchKernelGGL(rc_pick_kernel, dim3(1), dim3(kThreads), 0, stream, st, nbits, last ? 1 : 0,
                        reinterpret_cast<long long*>(stats));
     return hipGetLastError();
 }
