@@ -253,6 +253,31 @@ int tf_stage_backward_blocks(tf_ctx* ctx, void* hip_stream,
                              void* const* dX,
                              void* const* dW, tf_dtype dw_dtype,
                              int accumulate);
+/*
+ * Layers that share their input (in a transformer block q, k, v read the same
+ * activations, gate and up too): the gradient with respect to that input is the
+ * sum of the members' products,
+ *     dX_g = sum over l with input_group[l] == g of  dY_l * W_l^T,
+ * i.e. the product with the members' weights concatenated along the output
+ * features.  tf_stage_backward_shared is tf_stage_backward_blocks plus
+ *   input_group   host, n_layers, or NULL: -1 = a layer of its own; g >= 0 = member of group g
+ *                 (g < n_layers).  Members must have the same K_l and pass the SAME dX pointer;
+ *                 the sum is formed in the fp32 accumulators and rounded once.
+ * On the matrix cores the members are contraction segments of one problem (bf16, shapes as
+ * for tf_stage_backward); an fp32 stage falls back to one launch per member adding onto the
+ * previous one; a bf16 group with shapes the matrix-core kernel cannot take is TF_ERR_SHAPE.
+ * dW is per layer as before (each member has its own X pointer; they may be equal).
+ */
+int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
+                             int32_t n_layers, const tf_shape* shapes,
+                             int64_t T, tf_dtype io_dtype,
+                             const void* const* W, const void* const* X, const void* const* dY,
+                             const uint8_t* freeze_mask,
+                             const uint8_t* const* row_block_mask, int32_t block_rows,
+                             const int32_t* input_group,
+                             void* const* dX,
+                             void* const* dW, tf_dtype dw_dtype,
+                             int accumulate);
 int tf_select_row_blocks(int32_t n_layers, const tf_shape* shapes, int32_t block_rows,
                          double r, uint64_t seed, uint8_t* masks, int64_t* frozen_params);
 int tf_row_blocks_to_bits(tf_ctx* ctx, void* hip_stream,

@@ -155,6 +155,27 @@ def stage_backward_blocks(shapes: Sequence[tuple], T: int, W, X, dY, freeze_mask
             dW[l][rows] = dWs
 
 
+def stage_backward_shared(shapes: Sequence[tuple], T: int, W, X, dY, freeze_mask, input_group, dX, dW,
+                          accumulate: bool = False) -> None:
+    """Stage backward in which the layers of one input group share their input: the group's
+    input gradient is the sum of its members' dY_l W_l^T (the product with the weights
+    concatenated along the output features), written to every member's dX (they may be one
+    array).  input_group[l] = -1: a layer of its own.  dW is per layer as in stage_backward."""
+    L = len(shapes)
+    own = [np.zeros((T, k)) for k, n in shapes]
+    stage_backward(shapes, T, W, X, dY, freeze_mask, own, dW, accumulate)
+    groups = {}
+    for l in range(L):
+        g = -1 if input_group is None else int(input_group[l])
+        groups.setdefault(g if g >= 0 else -(l + 1), []).append(l)
+    for members in groups.values():
+        total = np.zeros_like(own[members[0]])
+        for l in members:
+            total += own[l]
+        for l in members:
+            dX[l][...] = total
+
+
 def sample_dx(dY, W, ts, ks) -> np.ndarray:
     """Single elements of the input gradient, one by one: dX[t, k] = sum_n dY[t, n] W[k, n]
     (Sec. 3.2.1, activation-gradient component).  dY [T, N] and W [K, N] may be float32 or

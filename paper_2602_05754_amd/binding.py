@@ -22,7 +22,7 @@ EXPORTED_SYMBOLS = [
     "tf_stability_scores", "tf_select_lowest", "tf_num_frozen",
     "tf_profile_enable", "tf_profile_collect",
     "tf_autofreeze_norms", "tf_autofreeze_scores", "tf_autofreeze_select", "tf_reconcile_mask",
-    "tf_stage_backward_blocks", "tf_select_row_blocks", "tf_row_blocks_to_bits",
+    "tf_stage_backward_blocks", "tf_stage_backward_shared", "tf_select_row_blocks", "tf_row_blocks_to_bits",
     "tf_pipeline_dag", "tf_dag_start_times", "tf_freeze_ratio_lp", "tf_actual_freeze_ratio",
 ]
 
@@ -95,6 +95,9 @@ def load_library():
     lib.tf_autofreeze_select.argtypes = [vp, i32, i32, f64, vp]
     lib.tf_stage_backward_blocks.restype = ctypes.c_int
     lib.tf_stage_backward_blocks.argtypes = [vp, vp, i32, vp, i64, ctypes.c_int, vp, vp, vp, vp, vp, i32, vp, vp,
+                                             ctypes.c_int, ctypes.c_int]
+    lib.tf_stage_backward_shared.restype = ctypes.c_int
+    lib.tf_stage_backward_shared.argtypes = [vp, vp, i32, vp, i64, ctypes.c_int, vp, vp, vp, vp, vp, i32, vp, vp, vp,
                                              ctypes.c_int, ctypes.c_int]
     lib.tf_select_row_blocks.restype = ctypes.c_int
     lib.tf_select_row_blocks.argtypes = [i32, vp, i32, f64, ctypes.c_uint64, vp, vp]
@@ -464,6 +467,34 @@ def tf_stage_backward_blocks(ctx, shapes: Sequence[tuple], T: int, io_dtype: int
                                       keep[0][1], keep[1][1], keep[2][1], fm_p, rm_p, int(block_rows),
                                       keep[3][1], keep[4][1], int(dw_dtype), 1 if accumulate else 0)
     _raise(ctx, rc, "tf_stage_backward_blocks")
+
+
+def tf_stage_backward_shared(ctx, shapes: Sequence[tuple], T: int, io_dtype: int,
+                             W, X, dY, freeze_mask, row_block_mask, block_rows: int, input_group, dX, dW, dw_dtype: int,
+                             accumulate: bool = False, stream=None) -> None:
+    """Stage backward in which layers of one input group share their dX (the sum of the members'
+    products).  See include/tf.h."""
+    lib = load_library()
+    L = len(shapes)
+    sh = np.ascontiguousarray(np.asarray(shapes, dtype=np.int64).reshape(L, 2))
+    fm, fm_p = _host(freeze_mask, np.uint8, L)
+    ig, ig_p = _host(input_group, np.int32, L)
+    for l in range(L):
+        K, N = int(sh[l, 0]), int(sh[l, 1])
+        frozen = fm is not None and fm[l]
+        if W is not None: _check_numel(W[l], K * N, io_dtype, f"W[{l}]")
+        if dY is not None: _check_numel(dY[l], T * N, io_dtype, f"dY[{l}]")
+        if dX is not None: _check_numel(dX[l], T * K, io_dtype, f"dX[{l}]")
+        if not frozen:
+            if X is not None: _check_numel(X[l], T * K, io_dtype, f"X[{l}]")
+            if dW is not None: _check_numel(dW[l], K * N, dw_dtype, f"dW[{l}]")
+    keep = [_ptr_array(s, L) for s in (W, X, dY, dX, dW)]
+    rm_keep, rm_p = _host_mask_table(row_block_mask, [tuple(map(int, r)) for r in sh], int(block_rows))
+    rc = lib.tf_stage_backward_shared(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
+                                      L, sh.ctypes.data, int(T), int(io_dtype),
+                                      keep[0][1], keep[1][1], keep[2][1], fm_p, rm_p, int(block_rows), ig_p,
+                                      keep[3][1], keep[4][1], int(dw_dtype), 1 if accumulate else 0)
+    _raise(ctx, rc, "tf_stage_backward_shared")
 
 
 def tf_select_row_blocks(shapes: Sequence[tuple], block_rows: int, r: float, seed: int):

@@ -213,27 +213,45 @@ __device__ __forceinline__ void fill_range(const Fill& f, FillRun& run, uint32_t
 // The fill stream of a workgroup: contraction steps of its tiles, one after the other.
 struct StreamPos {
     int64_t kstep_a, kstep_b;  // byte advance per contraction step of 64
-    int kt, nk;                // step inside the tile, steps of the tile
+    int kt, nk;                // step inside the segment, steps of the segment
     int vb;                    // virtual block index of the tile
-    int pi;                    // its problem
+    int pi;                    // its problem (the first segment's entry)
+    int seg, n_seg;            // contraction segment being fetched, segments of the problem
+    int m0, n0;                // tile origin
 };
+
+// Point the stream at the first step of segment c.seg of its tile.
+template <bool kTN>
+__device__ __forceinline__ void stream_set_segment(StreamPos& c, Fill& f, const GemmBatch& batch) {
+    const GemmProblem& P = batch.p[c.pi + c.seg];
+    const int64_t lda = P.lda, ldb = P.ldb;
+    f = make_fill<kTN>(static_cast<const uint16_t*>(P.A), static_cast<const uint16_t*>(P.B), lda, ldb, c.m0, c.n0);
+    c.kstep_a = kTN ? int64_t(kBK) * lda * 2 : kBK * 2;
+    c.kstep_b = kTN ? int64_t(kBK) * ldb * 2 : kBK * 2;
+    c.kt = 0; c.nk = P.Kc / kBK;
+}
 
 template <bool kTN>
 __device__ __forceinline__ void stream_set_tile(StreamPos& c, Fill& f, const GemmBatch& batch, int vb) {
     const TilePos tp = locate_tile(batch, logical_tile(vb, batch.total_tiles), c.pi);
-    const GemmProblem& P = batch.p[tp.pi];
-    const int64_t lda = P.lda, ldb = P.ldb;
-    f = make_fill<kTN>(static_cast<const uint16_t*>(P.A), static_cast<const uint16_t*>(P.B), lda, ldb, tp.m0, tp.n0);
-    c.kstep_a = kTN ? int64_t(kBK) * lda * 2 : kBK * 2;
-    c.kstep_b = kTN ? int64_t(kBK) * ldb * 2 : kBK * 2;
-    c.kt = 0; c.nk = P.Kc / kBK; c.vb = vb; c.pi = tp.pi;
+    c.vb = vb; c.pi = tp.pi; c.m0 = tp.m0; c.n0 = tp.n0;
+    c.seg = 0; c.n_seg = batch.p[tp.pi].n_seg;
+    stream_set_segment<kTN>(c, f, batch);
+}
+
+// Contraction steps of a tile: the sum over its problem's segments.
+__device__ __forceinline__ int tile_steps(const GemmBatch& batch, int pi) {
+    int n = 0;
+    const int n_seg = batch.p[pi].n_seg;
+    for (int q = 0; q < n_seg; ++q) n += batch.p[pi + q].Kc / kBK;
+    return n;
 }
 
 // Move `f` (the step the position stands on) to the next step of the stream, in two parts.
-// stream_guess is branch-free: it assumes that the tile goes on.  stream_settle puts things
-// right when the tile has ended.  Past the end of the workgroup's last tile the position stays
-// where it is: the last step is then fetched again, into a stage nobody reads any more, which
-// keeps the main loop free of special cases.
+// stream_guess is branch-free: it assumes that the segment goes on.  stream_settle puts things
+// right when it has ended: next segment of the tile, else next tile.  Past the end of the
+// workgroup's last tile the position stays where it is: the last step is then fetched again,
+// into a stage nobody reads any more, which keeps the main loop free of special cases.
 __device__ __forceinline__ void stream_guess(const StreamPos& c, Fill& f) {
     f.ga += c.kstep_a; f.gb += c.kstep_b;
 }
@@ -241,6 +259,9 @@ template <bool kTN>
 __device__ __forceinline__ void stream_settle(StreamPos& c, Fill& f, const GemmBatch& batch) {
     if (__builtin_expect(c.kt + 1 < c.nk, 1)) {
         ++c.kt;
+    } else if (c.seg + 1 < c.n_seg) {
+        ++c.seg;
+        stream_set_segment<kTN>(c, f, batch);
     } else if (c.vb + int(gridDim.x) < batch.total_tiles) {
         stream_set_tile<kTN>(c, f, batch, c.vb + int(gridDim.x));
     } else {
@@ -449,7 +470,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     // The tile being consumed.
     int cvb = int(blockIdx.x);
     TilePos ct = locate_tile(batch, logical_tile(cvb, total), 0);
-    int cnk = batch.p[ct.pi].Kc / kBK;
+    int cnk = tile_steps(batch, ct.pi);
 
     f32x16 acc[4][4];
     bf16x8 fa[2][4], fb[2][4];
@@ -541,7 +562,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
         cvb += stride;
         if (cvb >= total) break;
         ct = locate_tile(batch, logical_tile(cvb, total), ct.pi);
-        cnk = batch.p[ct.pi].Kc / kBK;
+        cnk = tile_steps(batch, ct.pi);
     }
     wait_direct_loads();      // nothing of this workgroup may still be in flight towards LDS
 }

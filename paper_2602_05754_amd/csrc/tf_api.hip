@@ -67,7 +67,21 @@ struct Planned {
     int64_t M, N, Kc;
     int64_t lda, ldb;       // row pitch of A, B in elements
     uint64_t row_bits;      // 256-row blocks that exist (MFMA kernel); all ones = dense
+    // further contraction segments whose products are summed into the same C (layers that
+    // share their input); matrix-core kernel only
+    std::vector<Planned> more;
+
+    int64_t total_kc() const {
+        int64_t k = Kc;
+        for (const Planned& q : more) k += q.Kc;
+        return k;
+    }
 };
+
+inline bool planned_mfma_ok(const Planned& it, Dtype in_dtype) {
+    return in_dtype == Dtype::BF16 && mfma_shape_ok(it.M, it.N, it.Kc, it.lda, it.ldb) &&
+           aligned16(it.A) && aligned16(it.B) && aligned16(it.C);
+}
 
 // Launch `items` in batches of at most kMaxProblemsPerLaunch, MFMA-eligible ones on the
 // matrix cores, the rest on the generic kernel.
@@ -75,16 +89,25 @@ hipError_t launch_planned(tf_ctx* ctx, hipStream_t stream, std::vector<Planned>&
                           Dtype in_dtype, Dtype out_dtype, bool accumulate) {
     std::vector<Planned> fast, slow;
     for (const Planned& it : items) {
-        if (in_dtype == Dtype::BF16 && mfma_shape_ok(it.M, it.N, it.Kc, it.lda, it.ldb) && aligned16(it.A) && aligned16(it.B) && aligned16(it.C)) fast.push_back(it);
-        else if (~it.row_bits != 0) return hipErrorInvalidValue;      // only the matrix-core kernel knows row bits
+        bool ok = planned_mfma_ok(it, in_dtype);
+        for (const Planned& q : it.more) ok = ok && planned_mfma_ok(q, in_dtype);
+        if (ok) fast.push_back(it);
+        else if (~it.row_bits != 0 || !it.more.empty()) return hipErrorInvalidValue;   // only the matrix-core kernel knows these
         else slow.push_back(it);
     }
     // Longest contraction first: the tail of a launch is then made of the cheapest tiles.
-    auto by_cost = [](const Planned& a, const Planned& b) { return a.Kc > b.Kc; };
+    auto by_cost = [](const Planned& a, const Planned& b) { return a.total_kc() > b.total_kc(); };
     std::stable_sort(fast.begin(), fast.end(), by_cost);
     std::stable_sort(slow.begin(), slow.end(), by_cost);
 
     GemmBatch batch;
+    auto fill = [](GemmProblem& gp, const Planned& it, int64_t tile_start, int n_seg) {
+        gp.A = it.A; gp.B = it.B; gp.C = it.C;
+        gp.M = int32_t(it.M); gp.N = int32_t(it.N); gp.Kc = int32_t(it.Kc);
+        gp.lda = int32_t(it.lda); gp.ldb = int32_t(it.ldb); gp.row_bits = it.row_bits;
+        gp.tile_start = int32_t(tile_start);
+        gp.n_seg = n_seg; gp.pad_ = 0;
+    };
     for (int pass = 0; pass < 2; ++pass) {
         const std::vector<Planned>& v = pass == 0 ? fast : slow;
         const int64_t tile = pass == 0 ? gemm_mfma_tile() : gemm_generic_tile();
@@ -92,17 +115,18 @@ hipError_t launch_planned(tf_ctx* ctx, hipStream_t stream, std::vector<Planned>&
         while (i < v.size()) {
             int n = 0;
             int64_t tiles = 0;
-            while (i < v.size() && n < kMaxProblemsPerLaunch) {
+            while (i < v.size()) {
                 const Planned& it = v[i];
+                const int slots = 1 + int(it.more.size());
+                if (slots > kMaxProblemsPerLaunch) return hipErrorInvalidValue;
+                if (n + slots > kMaxProblemsPerLaunch) break;
                 const int64_t nt = ((it.M + tile - 1) / tile) * ((it.N + tile - 1) / tile);
                 if (n > 0 && tiles + nt > 0x3fffffff) break;
-                GemmProblem& gp = batch.p[n];
-                gp.A = it.A; gp.B = it.B; gp.C = it.C;
-                gp.M = int32_t(it.M); gp.N = int32_t(it.N); gp.Kc = int32_t(it.Kc);
-                gp.lda = int32_t(it.lda); gp.ldb = int32_t(it.ldb); gp.row_bits = it.row_bits;
-                gp.tile_start = int32_t(tiles);
+                fill(batch.p[n], it, tiles, slots);
                 tiles += nt;
-                ++n; ++i;
+                ++n;
+                for (const Planned& q : it.more) { fill(batch.p[n], q, tiles, 1); ++n; }     // own no tiles
+                ++i;
             }
             batch.total_tiles = int32_t(tiles);
             const int kind = (layout == Layout::kNT ? TF_KERNEL_DX_MFMA : TF_KERNEL_DW_MFMA) + (pass == 0 ? 0 : 2);
@@ -223,12 +247,13 @@ int tf_profile_collect(tf_ctx* ctx, int32_t capacity, int32_t* kinds, float* ms,
 
 int tf_last_hip_error(const tf_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
 
-int tf_stage_backward_blocks(tf_ctx* ctx, void* hip_stream,
+int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
                              int32_t n_layers, const tf_shape* shapes,
                              int64_t T, tf_dtype io_dtype,
                              const void* const* W, const void* const* X, const void* const* dY,
                              const uint8_t* freeze_mask,
                              const uint8_t* const* row_block_mask, int32_t block_rows,
+                             const int32_t* input_group,
                              void* const* dX,
                              void* const* dW, tf_dtype dw_dtype,
                              int accumulate) {
@@ -252,6 +277,18 @@ int tf_stage_backward_blocks(tf_ctx* ctx, void* hip_stream,
             if (!(freeze_mask && freeze_mask[l])) any_unfrozen = true;
         }
         if (any_unfrozen && (!X || !dW)) return TF_ERR_INVALID_ARG;
+        if (input_group) {
+            // members of a group share their input: same K, same dX buffer; the first member leads
+            for (int32_t l = 0; l < n_layers; ++l) {
+                const int32_t g = input_group[l];
+                if (g < -1 || g >= n_layers) return TF_ERR_INVALID_ARG;
+                if (g < 0) continue;
+                int32_t lead = l;
+                for (int32_t q = 0; q < l; ++q) if (input_group[q] == g) { lead = q; break; }
+                if (shapes[lead].K != shapes[l].K) return TF_ERR_SHAPE;
+                if (dX[lead] != dX[l]) return TF_ERR_INVALID_ARG;
+            }
+        }
         for (int32_t l = 0; l < n_layers; ++l) {
             if (freeze_mask && freeze_mask[l]) continue;
             if (!X[l] || !dW[l]) return TF_ERR_INVALID_ARG;
@@ -270,12 +307,44 @@ int tf_stage_backward_blocks(tf_ctx* ctx, void* hip_stream,
     const Dtype in_dt = to_dtype(io_dtype);
     const int64_t in_size = io_dtype == TF_BF16 ? 2 : 4, dw_size = dw_dtype == TF_BF16 ? 2 : 4;
 
-    // input gradients: every layer, whatever the masks say
+    // input gradients: every layer, whatever the masks say.  Layers that share their input are
+    // segments of one problem: their products are summed in the accumulators and rounded once.
     std::vector<Planned> plan;
     plan.reserve(n_layers);
-    for (int32_t l = 0; l < n_layers; ++l)
-        plan.push_back(Planned{dY[l], W[l], dX[l], T, shapes[l].K, shapes[l].N, shapes[l].N, shapes[l].N, ~0ull});
-    hipError_t e = launch_planned(ctx, stream, plan, Layout::kNT, in_dt, in_dt, false);
+    bool grouped_slow = false;
+    {
+        std::vector<int32_t> lead_slot(n_layers, -1);          // group id -> index in plan
+        for (int32_t l = 0; l < n_layers; ++l) {
+            Planned it{dY[l], W[l], dX[l], T, shapes[l].K, shapes[l].N, shapes[l].N, shapes[l].N, ~0ull, {}};
+            const int32_t g = input_group ? input_group[l] : -1;
+            if (g >= 0 && lead_slot[g] >= 0) plan[lead_slot[g]].more.push_back(it);
+            else { if (g >= 0) lead_slot[g] = int32_t(plan.size()); plan.push_back(it); }
+        }
+        for (const Planned& it : plan) {
+            if (it.more.empty()) continue;
+            bool ok = planned_mfma_ok(it, in_dt);
+            for (const Planned& q : it.more) ok = ok && planned_mfma_ok(q, in_dt);
+            if (!ok) grouped_slow = true;
+        }
+    }
+    hipError_t e = hipSuccess;
+    if (!grouped_slow) {
+        e = launch_planned(ctx, stream, plan, Layout::kNT, in_dt, in_dt, false);
+    } else {
+        // A group that the matrix-core kernel cannot take: member after member, each launch adding
+        // onto the one before.  That needs an fp32 output (the fp32 configuration).
+        if (in_dt != Dtype::F32) return TF_ERR_SHAPE;
+        size_t depth = 0;
+        for (const Planned& it : plan) depth = std::max(depth, it.more.size());
+        for (size_t k = 0; k <= depth && e == hipSuccess; ++k) {
+            std::vector<Planned> round;
+            for (const Planned& it : plan) {
+                if (k == 0) { Planned h = it; h.more.clear(); round.push_back(h); }
+                else if (k <= it.more.size()) round.push_back(it.more[k - 1]);
+            }
+            e = launch_planned(ctx, stream, round, Layout::kNT, in_dt, in_dt, k > 0);
+        }
+    }
     if (e != hipSuccess) return hip_fail(ctx, e);
 
     // weight gradients: what is frozen - a layer, or a block of rows of one - is simply not
@@ -286,7 +355,7 @@ int tf_stage_backward_blocks(tf_ctx* ctx, void* hip_stream,
         const int64_t K = shapes[l].K, N = shapes[l].N;
         const uint8_t* rm = row_block_mask ? row_block_mask[l] : nullptr;
         if (!rm) {
-            plan.push_back(Planned{X[l], dY[l], dW[l], K, N, T, K, N, ~0ull});
+            plan.push_back(Planned{X[l], dY[l], dW[l], K, N, T, K, N, ~0ull, {}});
             continue;
         }
         const int64_t nb = K / block_rows;
@@ -301,7 +370,7 @@ int tf_stage_backward_blocks(tf_ctx* ctx, void* hip_stream,
             for (int64_t b = 0; b < nb; ++b)
                 if (!rm[b])
                     for (int64_t q = 0; q < per; ++q) { bits |= 1ull << (b * per + q); rows += tile; }
-            if (rows > 0) plan.push_back(Planned{X[l], dY[l], dW[l], rows, N, T, K, N, rows == K ? ~0ull : bits});
+            if (rows > 0) plan.push_back(Planned{X[l], dY[l], dW[l], rows, N, T, K, N, rows == K ? ~0ull : bits, {}});
             continue;
         }
         // Otherwise each run of unfrozen row blocks is one problem: columns [k0, k1) of X
@@ -312,7 +381,7 @@ int tf_stage_backward_blocks(tf_ctx* ctx, void* hip_stream,
             while (e1 < nb && !rm[e1]) ++e1;
             const int64_t k0 = b * block_rows, rows = (e1 - b) * block_rows;
             plan.push_back(Planned{static_cast<const char*>(X[l]) + k0 * in_size, dY[l],
-                                   static_cast<char*>(dW[l]) + k0 * N * dw_size, rows, N, T, K, N, ~0ull});
+                                   static_cast<char*>(dW[l]) + k0 * N * dw_size, rows, N, T, K, N, ~0ull, {}});
             b = e1;
         }
     }
@@ -329,8 +398,21 @@ int tf_stage_backward(tf_ctx* ctx, void* hip_stream,
                       void* const* dX,
                       void* const* dW, tf_dtype dw_dtype,
                       int accumulate) {
-    return tf_stage_backward_blocks(ctx, hip_stream, n_layers, shapes, T, io_dtype, W, X, dY, freeze_mask,
-                                    nullptr, 0, dX, dW, dw_dtype, accumulate);
+    return tf_stage_backward_shared(ctx, hip_stream, n_layers, shapes, T, io_dtype, W, X, dY, freeze_mask,
+                                    nullptr, 0, nullptr, dX, dW, dw_dtype, accumulate);
+}
+
+int tf_stage_backward_blocks(tf_ctx* ctx, void* hip_stream,
+                             int32_t n_layers, const tf_shape* shapes,
+                             int64_t T, tf_dtype io_dtype,
+                             const void* const* W, const void* const* X, const void* const* dY,
+                             const uint8_t* freeze_mask,
+                             const uint8_t* const* row_block_mask, int32_t block_rows,
+                             void* const* dX,
+                             void* const* dW, tf_dtype dw_dtype,
+                             int accumulate) {
+    return tf_stage_backward_shared(ctx, hip_stream, n_layers, shapes, T, io_dtype, W, X, dY, freeze_mask,
+                                    row_block_mask, block_rows, nullptr, dX, dW, dw_dtype, accumulate);
 }
 
 int tf_masked_adamw(tf_ctx* ctx, void* hip_stream,

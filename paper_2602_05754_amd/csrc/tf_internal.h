@@ -32,6 +32,12 @@ struct GemmProblem {
     // bit.  All ones = dense.  This is how frozen row blocks of a weight gradient are skipped
     // inside one grouped launch without touching their rows.
     uint64_t row_bits;
+    // MFMA kernel only: the contraction of this problem continues over the next n_seg - 1 entries
+    // of the batch (their A, B, Kc, lda, ldb; they own no tiles: tile_start = this problem's end).
+    // C = sum over the segments of A_i B_i^T - several layers that share their input give ONE
+    // input gradient, accumulated in fp32 and rounded once.  1 = an ordinary problem.
+    int32_t n_seg;
+    int32_t pad_;
 };
 
 constexpr int kMaxProblemsPerLaunch = 64;

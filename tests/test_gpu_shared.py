@@ -1,0 +1,100 @@
+"""GPU parity of shared-input groups: layers of one group get ONE input gradient,
+the sum of the members' products (Sec. 3.2.1, activation-gradient component;
+the oracle's definition is the product with the concatenated weights).  Bounds
+as for the stage backward: relative Frobenius 1e-2 (bf16) / 1e-5 (fp32)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+import paper_2602_05754_amd as tf
+from gpu_util import CODE, TDT, TOL, canary, dev, host64, raw_bytes, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = tf.Context(0)
+    yield c
+    c.close()
+
+
+def _block_shapes(d, kv, ffn):
+    return [(d, d), (d, kv), (d, kv), (d, d), (d, ffn), (d, ffn), (ffn, d)], [0, 0, 0, -1, 1, 1, -1]
+
+
+def _run(ctx, shapes, groups, T, dtype, freeze_mask, seed):
+    rs = np.random.default_rng(seed)
+    f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    W = [f32(rs.standard_normal(s) * 0.02) for s in shapes]
+    X = [f32(rs.standard_normal((T, k))) for k, n in shapes]
+    dY = [f32(rs.standard_normal((T, n)) * 1e-3) for k, n in shapes]
+    if dtype == "bf16":
+        W, X, dY = ([wl.round_to_bf16(a) for a in t] for t in (W, X, dY))
+    f64 = lambda t: [np.asarray(a, dtype=np.float64) for a in t]
+    L = len(shapes)
+    fm = np.zeros(L, np.uint8) if freeze_mask is None else np.asarray(freeze_mask, np.uint8)
+    ref_dX = [np.zeros((T, k)) for k, n in shapes]
+    ref_dW = [np.zeros(s) for s in shapes]
+    oracle.stage_backward_shared(shapes, T, f64(W), f64(X), f64(dY), fm, groups, ref_dX, ref_dW)
+    # one dX buffer per group, shared by its members
+    bufs = {}
+    gdX = []
+    for l, (k, n) in enumerate(shapes):
+        g = groups[l]
+        key = g if g >= 0 else -(l + 1)
+        if key not in bufs:
+            bufs[key] = canary((T, k), TDT[dtype])
+        gdX.append(bufs[key])
+    gdW = [canary(s, TDT[dtype]) for s in shapes]
+    before = [t.clone() for t in gdW]
+    tf.tf_stage_backward_shared(ctx, shapes, T, CODE[dtype], [dev(a, dtype) for a in W], [dev(a, dtype) for a in X],
+                                [dev(a, dtype) for a in dY], fm, None, 0, groups, gdX, gdW, CODE[dtype])
+    torch.cuda.synchronize()
+    for l in range(L):
+        assert rel_fro(host64(gdX[l]), ref_dX[l]) <= TOL[dtype], f"dX[{l}]"
+        if fm[l]:
+            assert raw_bytes(gdW[l]) == raw_bytes(before[l])
+        else:
+            assert rel_fro(host64(gdW[l]), ref_dW[l]) <= TOL[dtype], f"dW[{l}]"
+    return gdX, ref_dX
+
+
+def test_bf16_groups_as_contraction_segments_on_the_matrix_cores(ctx):
+    shapes, groups = _block_shapes(512, 256, 768)
+    # two blocks, so that grouped and plain problems of several contraction lengths share one launch
+    _run(ctx, shapes * 2, groups + [2, 2, 2, -1, 3, 3, -1], 512, "bf16", [0, 1, 0, 0, 0, 0, 1] * 2, seed=3)
+
+
+def test_grouped_sum_is_rounded_once(ctx):
+    # the grouped result is closer to the exact sum than the bf16 sum of separately rounded members
+    shapes, groups = [(256, 256), (256, 256), (256, 256)], [0, 0, 0]
+    gdX, ref = _run(ctx, shapes, groups, 256, "bf16", None, seed=4)
+    err_grouped = rel_fro(host64(gdX[0]), ref[0])
+    assert err_grouped <= 2.0 ** -8                       # a single bf16 rounding
+
+
+def test_fp32_groups_fall_back_to_one_launch_per_member(ctx):
+    cfg = wl.CONFIGS[1]
+    groups = [0, 0, 0, -1, 1, 1, -1] * cfg.blocks
+    groups = [g if g < 0 else g + 2 * (i // 7) for i, g in enumerate(groups)]
+    _run(ctx, cfg.shapes, groups, 64, "f32", None, seed=5)
+
+
+def test_bf16_group_with_ragged_shapes_is_refused(ctx):
+    shapes, groups = [(256, 688), (256, 688)], [0, 0]      # 688 is not a multiple of the tile edge
+    A = torch.zeros(256 * 688 * 2, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(tf.TfError) as e:
+        tf.tf_stage_backward_shared(ctx, shapes, 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, groups, [A, A], [A, A], tf.TF_BF16)
+    assert e.value.code == -2
+
+
+def test_group_members_must_share_the_buffer_and_the_width(ctx):
+    A = torch.zeros(256 * 256, dtype=torch.bfloat16, device="cuda")
+    B = torch.zeros(256 * 256, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(tf.TfError):
+        tf.tf_stage_backward_shared(ctx, [(256, 256)] * 2, 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, [0, 0], [A, B], [A, A], tf.TF_BF16)
+    with pytest.raises(tf.TfError):
+        tf.tf_stage_backward_shared(ctx, [(256, 256), (128, 256)], 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, [0, 0], [A, A], [A, A], tf.TF_BF16)

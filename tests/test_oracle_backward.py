@@ -179,3 +179,32 @@ def test_sampled_elements_equal_the_full_oracle():
     got = oracle.sample_dx(dY[0].astype(np.float32), W[0].astype(np.float32), ts, ks)
     exp = (dY[0].astype(np.float32).astype(np.float64) @ W[0].astype(np.float32).astype(np.float64).T)[ts, ks]
     np.testing.assert_allclose(got, exp, rtol=1e-13, atol=1e-14)
+
+
+def test_shared_input_gradient_is_the_product_with_the_concatenated_weights():
+    """q, k, v (and gate, up) read the same activations: the gradient with respect to them is the
+    sum of the members' products = dY_cat W_cat^T with the weights concatenated along the output
+    features (Sec. 3.2.1: the activation-gradient component; the stage's linears as in a block)."""
+    rng = np.random.default_rng(12)
+    T, d, kv, ffn = 7, 6, 3, 10
+    shapes = [(d, d), (d, kv), (d, kv), (d, d), (d, ffn), (d, ffn), (ffn, d)]
+    groups = [0, 0, 0, -1, 1, 1, -1]
+    W = [rng.standard_normal(s) for s in shapes]
+    X = [rng.standard_normal((T, k)) for k, n in shapes]
+    dY = [rng.standard_normal((T, n)) for k, n in shapes]
+    dX = [np.zeros((T, k)) for k, n in shapes]
+    dW = [np.zeros(s) for s in shapes]
+    oracle.stage_backward_shared(shapes, T, W, X, dY, np.zeros(7, np.uint8), groups, dX, dW)
+    qkv = np.concatenate(dY[0:3], axis=1) @ np.concatenate(W[0:3], axis=1).T
+    gu = np.concatenate(dY[4:6], axis=1) @ np.concatenate(W[4:6], axis=1).T
+    for l in (0, 1, 2):
+        assert np.allclose(dX[l], qkv, atol=1e-12)
+    for l in (4, 5):
+        assert np.allclose(dX[l], gu, atol=1e-12)
+    assert np.allclose(dX[3], dY[3] @ W[3].T, atol=1e-12) and np.allclose(dX[6], dY[6] @ W[6].T, atol=1e-12)
+    for l in range(7):
+        assert np.allclose(dW[l], X[l].T @ dY[l], atol=1e-12)           # weight gradients stay per layer
+    # no groups: the plain backward
+    dX2 = [np.zeros((T, k)) for k, n in shapes]
+    oracle.stage_backward_shared(shapes, T, W, X, dY, np.zeros(7, np.uint8), None, dX2, [np.zeros(s) for s in shapes])
+    assert all(np.allclose(a, g @ w.T, atol=1e-12) for a, g, w in zip(dX2, dY, W))
