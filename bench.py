@@ -47,11 +47,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7],
+    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7, 8],
                     help="config id: 2 = LLaMA-1B-shaped stage (the benchmark line); 3 = LLaMA-8B stage; "
                          "4 = elementwise pass only, Bernoulli element masks; 5 = 8 microbatches with fp32 dW accumulation; "
                          "6 = selection steps on the 8B stage's tensors (AutoFreeze norms, Alg. 2 budget reconciliation); "
-                         "7 = the benchmark stage with sub-tensor freezing (256-row blocks drawn under the parameter budget r P)")
+                         "7 = the benchmark stage with sub-tensor freezing (256-row blocks drawn under the parameter budget r P); "
+                         "8 = the benchmark stage with q/k/v and gate/up sharing their input (one dX per group)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -189,7 +190,7 @@ def main():
         print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n,
                           "GBps": 2 * n / dt / 1e9}), flush=True)
         return
-    cfg = wl.CONFIGS[{6: 3, 7: 2}.get(args.workload, args.workload)]
+    cfg = wl.CONFIGS[{6: 3, 7: 2, 8: 2}.get(args.workload, args.workload)]
     ctx = tf.Context(0)
     if args.workload == 4:
         return bench_elementwise(args, cfg, ctx, wl, tf, torch)
@@ -199,6 +200,8 @@ def main():
         return bench_selection(args, cfg, ctx, wl, tf, torch)
     if args.workload == 7:
         return bench_row_blocks(args, cfg, ctx, wl, tf, torch)
+    if args.workload == 8:
+        return bench_shared_inputs(args, cfg, ctx, wl, tf, torch)
     st = Stage(cfg, wl, tf, torch)
     L, T, P = st.L, st.T, cfg.n_params
 
@@ -436,6 +439,33 @@ def bench_row_blocks(args, cfg, ctx, wl, tf, torch):
     for x in rows[1:-1]:
         x["eta_backward"] = (b0 - x["backward_ms"]) / (x["phi"] * (b0 - b1))
     print(json.dumps({"workload": f"cfg2 stage with 256-row-block freezing, L={L} tensors, P={P} params, T={T}", "rows": rows}), flush=True)
+
+
+def bench_shared_inputs(args, cfg, ctx, wl, tf, torch):
+    """The benchmark stage (cfg 2) with q/k/v and gate/up of every block sharing their input: one dX
+    per group (the members are contraction segments of one problem), against the plain backward in
+    which every layer writes its own dX.  Same FLOPs; 16 instead of 28 dX outputs."""
+    st = Stage(cfg, wl, tf, torch)
+    L, T, P = st.L, st.T, cfg.n_params
+    groups = []
+    for b in range(cfg.blocks):
+        groups += [2 * b, 2 * b, 2 * b, -1, 2 * b + 1, 2 * b + 1, -1]
+    shared = {}
+    dX = []
+    for l in range(L):
+        key = groups[l] if groups[l] >= 0 else -(l + 1)
+        shared.setdefault(key, st.dX[l])
+        dX.append(shared[key])
+    frozen = np.ones(L, np.uint8)
+    out = {}
+    for name, fn in (("plain", lambda: tf.tf_stage_backward(ctx, st.shapes, T, tf.TF_BF16, st.W, None, st.dY, frozen, st.dX, None, tf.TF_BF16)),
+                     ("shared", lambda: tf.tf_stage_backward_shared(ctx, st.shapes, T, tf.TF_BF16, st.W, None, st.dY, frozen, None, 0,
+                                                                    groups, dX, None, tf.TF_BF16))):
+        dt, prof = _timed(ctx, torch, fn, args.steps, args.warmup)
+        ms = float(np.mean([t for k, t in prof if k == "dx_mfma"]))
+        out[name] = {"dx_ms": ms, "dx_tflops": 2.0 * T * P / ms / 1e9}
+        log(f"dX {name}: {ms:.3f} ms, {out[name]['dx_tflops']:.0f} TFLOP/s")
+    print(json.dumps({"workload": f"cfg2 stage, input gradients with and without shared-input groups, T={T}", **out}), flush=True)
 
 
 def bench_selection(args, cfg, ctx, wl, tf, torch):

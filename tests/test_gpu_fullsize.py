@@ -294,3 +294,35 @@ def test_llama1b_stage_with_row_block_freezing_at_full_size(ctx):
         for b in np.flatnonzero(masks[l]):
             rows = slice(b * 256, (b + 1) * 256)
             assert torch.equal(gdW[l][rows].view(torch.int16), before[l][rows].view(torch.int16)), f"frozen rows of dW[{l}] touched"
+
+
+def test_llama1b_stage_with_shared_inputs_at_full_size(ctx):
+    """cfg 2 at full size with q/k/v and gate/up of every block sharing their input: sampled
+    elements of the grouped dX against the sum of one-by-one oracle dots over the members."""
+    cfg = wl.CONFIGS[2]
+    sh, T, L = cfg.shapes, cfg.T, cfg.n_layers
+    groups = []
+    for b in range(cfg.blocks):
+        groups += [2 * b, 2 * b, 2 * b, -1, 2 * b + 1, 2 * b + 1, -1]
+    host = _gen(cfg)
+    gW = [dev(h[0], "bf16") for h in host]
+    gdY = [dev(h[2], "bf16") for h in host]
+    bufs, gdX = {}, []
+    for l, (k, n) in enumerate(sh):
+        key = groups[l] if groups[l] >= 0 else -(l + 1)
+        if key not in bufs:
+            bufs[key] = canary((T, k), torch.bfloat16)
+        gdX.append(bufs[key])
+    tf.tf_stage_backward_shared(ctx, sh, T, tf.TF_BF16, gW, None, gdY, np.ones(L, np.uint8), None, 0, groups, gdX, None, tf.TF_BF16)
+    torch.cuda.synchronize()
+    rs = np.random.default_rng(41)
+    seen = set()
+    for l, (k, n) in enumerate(sh):
+        key = groups[l] if groups[l] >= 0 else -(l + 1)
+        if key in seen:
+            continue
+        seen.add(key)
+        members = [q for q in range(L) if (groups[q] if groups[q] >= 0 else -(q + 1)) == key]
+        ts, ks = _tile_samples(rs, T, k, per_tile=1)
+        exact = sum(oracle.sample_dx(host[q][2], host[q][0], ts, ks) for q in members)
+        _check(_gather(gdX[l], ts, ks), exact, f"grouped dX of layers {members}")
