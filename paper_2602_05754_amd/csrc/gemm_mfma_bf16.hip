@@ -20,6 +20,10 @@
 // The first step of a tile multiplies into a zero constant instead of clearing
 // 256 registers.  The epilogue turns 32-row blocks around in 8 KB of LDS per wave
 // that lies beyond the two stages, so it never collides with the fills in flight.
+// A problem may name which 256-row blocks of its output exist (row_bits: frozen row
+// blocks of a weight gradient have no tiles) and may continue its contraction over
+// the descriptors that follow it (n_seg: layers that share their input give one
+// input gradient); the stream treats a new segment like a new tile without epilogue.
 //
 //   kNT stage: [256 rows][64 contraction] per operand, 16-byte chunks of a row
 //              XOR-swizzled; MFMA operands are plain 128-bit LDS reads.
