@@ -124,19 +124,27 @@ __device__ __forceinline__ TilePos locate_tile(const GemmBatch& batch, int lt, i
 //   kTN: that KB is contraction rows T = 2 (4 p + w) + lane/32, 16-byte slot lane%32 of
 //        each; logical 64-byte block = physical block ^ (T & 3).
 // ---------------------------------------------------------------------------------------------
-struct Fill {
+struct Run {
+    // One contraction segment of one tile, as the fill stream sees it.  Loads p = 0..3 of an
+    // operand go through (ga, va[p]), loads 4..7 through (ga2, va[p - 4]).
     const char* ga;           // wave-uniform global byte address: tile origin + contraction offset
+    const char* ga2;
     const char* gb;
-    int64_t pstep_a, pstep_b; // wave-uniform byte distance between loads p and p + 1
-    uint32_t voff_a[2];       // per-lane byte offsets (even / odd p; they differ only for kNT)
-    uint32_t voff_b[2];
+    const char* gb2;
+    uint32_t ks_a, ks_b;      // byte advance per contraction step of 64 (kTN; a constant for kNT)
+    int nk;                   // steps of the segment
+    uint32_t va[4];           // per-lane byte offsets; they depend on the row pitch only
+    uint32_t vb[4];
 };
 
 template <bool kTN>
-__device__ __forceinline__ Fill make_fill(const uint16_t* A, const uint16_t* B, int64_t lda, int64_t ldb,
-                                          int m0, int n0) {
+__device__ __forceinline__ Run make_run(const GemmProblem& P, int m0, int n0) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    Fill f;
+    const int64_t lda = P.lda, ldb = P.ldb;
+    const uint16_t* A = static_cast<const uint16_t*>(P.A);
+    const uint16_t* B = static_cast<const uint16_t*>(P.B);
+    Run f;
+    f.nk = P.Kc / kBK;
     if (kTN) {
         const int T = 2 * w + (lane >> 5);                     // + 8 p
         const int slot = lane & 31;
@@ -144,22 +152,29 @@ __device__ __forceinline__ Fill make_fill(const uint16_t* A, const uint16_t* B, 
         const int col = blk * 32 + (slot & 3) * 8;             // element offset inside the 256-wide tile row
         f.ga = reinterpret_cast<const char*>(A + m0);
         f.gb = reinterpret_cast<const char*>(B + n0);
-        f.voff_a[0] = f.voff_a[1] = uint32_t((int64_t(T) * lda + col) * 2);
-        f.voff_b[0] = f.voff_b[1] = uint32_t((int64_t(T) * ldb + col) * 2);
-        f.pstep_a = 2 * kWaves * lda * 2; f.pstep_b = 2 * kWaves * ldb * 2;
+        f.ga2 = f.ga + 8 * kWaves * lda * 2;
+        f.gb2 = f.gb + 8 * kWaves * ldb * 2;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            f.va[p] = uint32_t((int64_t(T + 2 * kWaves * p) * lda + col) * 2);
+            f.vb[p] = uint32_t((int64_t(T + 2 * kWaves * p) * ldb + col) * 2);
+        }
+        f.ks_a = uint32_t(kBK * lda * 2); f.ks_b = uint32_t(kBK * ldb * 2);
     } else {
         const int r = 8 * w + (lane >> 3);                     // + 32 p
         const int pc = lane & 7;
         f.ga = reinterpret_cast<const char*>(A + int64_t(m0) * lda);
         f.gb = reinterpret_cast<const char*>(B + int64_t(n0) * ldb);
+        f.ga2 = f.ga + 32 * kWaves * lda * 2;
+        f.gb2 = f.gb + 32 * kWaves * ldb * 2;
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {                          // p even / odd
-            const int R = r + 8 * kWaves * q;
-            const int c = pc ^ ((R ^ (R >> 3)) & 7);
-            f.voff_a[q] = uint32_t((int64_t(r) * lda + c * 8) * 2);
-            f.voff_b[q] = uint32_t((int64_t(r) * ldb + c * 8) * 2);
+        for (int p = 0; p < 4; ++p) {
+            const int R = r + 8 * kWaves * p;
+            const int c = pc ^ ((R ^ (R >> 3)) & 7);           // the same for p and p + 4
+            f.va[p] = uint32_t((int64_t(R) * lda + c * 8) * 2);
+            f.vb[p] = uint32_t((int64_t(R) * ldb + c * 8) * 2);
         }
-        f.pstep_a = 8 * kWaves * lda * 2; f.pstep_b = 8 * kWaves * ldb * 2;
+        f.ks_a = f.ks_b = 0;
     }
     return f;
 }
@@ -185,62 +200,72 @@ __device__ __forceinline__ void wait_direct_loads() {
     __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0), other counters untouched
 }
 
-// Running global addresses of a stage fill: one load per operand and call of fill_next.
-struct FillRun {
-    const char* a;
-    const char* b;
-};
-// Start at load pair p0 (load p of an operand fetches KB number 4 p + w of its tile).
-template <int p0>
-__device__ __forceinline__ FillRun fill_begin(const Fill& f) {
-    return FillRun{f.ga + p0 * f.pstep_a, f.gb + p0 * f.pstep_b};
-}
 // Issue load number q (0 .. kLoads-1) of a stage fill: even q fetch operand A, odd q operand
-// B, load pair p = q / 2.  lds_wave_base is the LDS byte address of the stage (of operand A)
-// plus 1 KB times the wave index.
+// B, load pair p = q / 2 (load p of an operand fetches KB number 4 p + w of its tile).
+// lds_wave_base is the LDS byte address of the stage (of operand A) plus 1 KB times the wave
+// index.  Nothing but the load itself: every address is ready in a register.
 template <int q>
-__device__ __forceinline__ void fill_next(const Fill& f, FillRun& run, uint32_t lds_wave_base) {
+__device__ __forceinline__ void fill_next(const Run& f, uint32_t lds_wave_base) {
     constexpr int p = q >> 1;
     constexpr int kOff = p * kWaves * 1024;
-    if ((q & 1) == 0) { direct_load_16B<kOff>(run.a, f.voff_a[p & 1], lds_wave_base); run.a += f.pstep_a; }
-    else              { direct_load_16B<kOperandB + kOff>(run.b, f.voff_b[p & 1], lds_wave_base); run.b += f.pstep_b; }
+    if ((q & 1) == 0) direct_load_16B<kOff>(p < 4 ? f.ga : f.ga2, f.va[p & 3], lds_wave_base);
+    else              direct_load_16B<kOperandB + kOff>(p < 4 ? f.gb : f.gb2, f.vb[p & 3], lds_wave_base);
 }
 
 template <int q, int end>
-__device__ __forceinline__ void fill_range(const Fill& f, FillRun& run, uint32_t lds_wave_base) {
+__device__ __forceinline__ void fill_range(const Run& f, uint32_t lds_wave_base) {
     if constexpr (q < end) {
-        fill_next<q>(f, run, lds_wave_base);
-        fill_range<q + 1, end>(f, run, lds_wave_base);
+        fill_next<q>(f, lds_wave_base);
+        fill_range<q + 1, end>(f, lds_wave_base);
     }
 }
 
-// The fill stream of a workgroup: contraction steps of its tiles, one after the other.
-struct StreamPos {
-    int64_t kstep_a, kstep_b;  // byte advance per contraction step of 64
-    int kt, nk;                // step inside the segment, steps of the segment
-    int vb;                    // virtual block index of the tile
-    int pi;                    // its problem (the first segment's entry)
-    int seg, n_seg;            // contraction segment being fetched, segments of the problem
+template <class T>
+__device__ __forceinline__ T pick(bool c, T a, T b) { return c ? a : b; }
+// Byte advance of an operand per contraction step: 64 rows of its pitch, or 64 elements.
+template <bool kTN>
+__device__ __forceinline__ uint32_t step_bytes(uint32_t ks) { return kTN ? ks : uint32_t(kBK * 2); }
+
+// The fill stream of a workgroup: the contraction segments ("runs") of its tiles, one after the
+// other.  `cur` is the run being fetched and `kt` the step inside it whose loads are issued
+// next; `nxt` is the run after it, worked out ahead of time so that going from one run to the
+// next inside the main loop is a handful of selects and no branch.
+struct StreamPos {             // identifies the run held in `nxt`
+    int vb;                    // virtual block index of its tile
+    int pi;                    // the tile's problem (the first segment's entry)
+    int seg, n_seg;            // which contraction segment, segments of the problem
     int m0, n0;                // tile origin
 };
 
-// Point the stream at the first step of segment c.seg of its tile.
 template <bool kTN>
-__device__ __forceinline__ void stream_set_segment(StreamPos& c, Fill& f, const GemmBatch& batch) {
-    const GemmProblem& P = batch.p[c.pi + c.seg];
-    const int64_t lda = P.lda, ldb = P.ldb;
-    f = make_fill<kTN>(static_cast<const uint16_t*>(P.A), static_cast<const uint16_t*>(P.B), lda, ldb, c.m0, c.n0);
-    c.kstep_a = kTN ? int64_t(kBK) * lda * 2 : kBK * 2;
-    c.kstep_b = kTN ? int64_t(kBK) * ldb * 2 : kBK * 2;
-    c.kt = 0; c.nk = P.Kc / kBK;
-}
-
-template <bool kTN>
-__device__ __forceinline__ void stream_set_tile(StreamPos& c, Fill& f, const GemmBatch& batch, int vb) {
+__device__ __forceinline__ Run stream_first(StreamPos& c, const GemmBatch& batch, int vb) {
     const TilePos tp = locate_tile(batch, logical_tile(vb, batch.total_tiles), c.pi);
     c.vb = vb; c.pi = tp.pi; c.m0 = tp.m0; c.n0 = tp.n0;
     c.seg = 0; c.n_seg = batch.p[tp.pi].n_seg;
-    stream_set_segment<kTN>(c, f, batch);
+    return make_run<kTN>(batch.p[c.pi], c.m0, c.n0);
+}
+
+// `cur` has just become the run that c identifies (step 0 of it): work out the run after it.
+// Past the workgroup's last run the stand-in is that run's last step as a run of its own: it
+// is then fetched again, into a stage nobody reads any more, for the two steps by which the
+// matrix cores lag behind the stream, which keeps the main loop free of special cases.
+template <bool kTN>
+__device__ __forceinline__ void stream_prepare(StreamPos& c, const Run& cur, Run& nxt, const GemmBatch& batch) {
+    if (c.seg + 1 < c.n_seg) {
+        ++c.seg;
+        nxt = make_run<kTN>(batch.p[c.pi + c.seg], c.m0, c.n0);
+    } else if (c.vb + int(gridDim.x) < batch.total_tiles) {
+        nxt = stream_first<kTN>(c, batch, c.vb + int(gridDim.x));
+    } else {
+        const int64_t last_a = int64_t(cur.nk - 1) * step_bytes<kTN>(cur.ks_a);
+        const int64_t last_b = int64_t(cur.nk - 1) * step_bytes<kTN>(cur.ks_b);
+        nxt.ga = cur.ga + last_a; nxt.ga2 = cur.ga2 + last_a;
+        nxt.gb = cur.gb + last_b; nxt.gb2 = cur.gb2 + last_b;
+        nxt.ks_a = cur.ks_a; nxt.ks_b = cur.ks_b;
+        nxt.nk = 1;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) { nxt.va[p] = cur.va[p]; nxt.vb[p] = cur.vb[p]; }
+    }
 }
 
 // Contraction steps of a tile: the sum over its problem's segments.
@@ -249,28 +274,6 @@ __device__ __forceinline__ int tile_steps(const GemmBatch& batch, int pi) {
     const int n_seg = batch.p[pi].n_seg;
     for (int q = 0; q < n_seg; ++q) n += batch.p[pi + q].Kc / kBK;
     return n;
-}
-
-// Move `f` (the step the position stands on) to the next step of the stream, in two parts.
-// stream_guess is branch-free: it assumes that the segment goes on.  stream_settle puts things
-// right when it has ended: next segment of the tile, else next tile.  Past the end of the
-// workgroup's last tile the position stays where it is: the last step is then fetched again,
-// into a stage nobody reads any more, which keeps the main loop free of special cases.
-__device__ __forceinline__ void stream_guess(const StreamPos& c, Fill& f) {
-    f.ga += c.kstep_a; f.gb += c.kstep_b;
-}
-template <bool kTN>
-__device__ __forceinline__ void stream_settle(StreamPos& c, Fill& f, const GemmBatch& batch) {
-    if (__builtin_expect(c.kt + 1 < c.nk, 1)) {
-        ++c.kt;
-    } else if (c.seg + 1 < c.n_seg) {
-        ++c.seg;
-        stream_set_segment<kTN>(c, f, batch);
-    } else if (c.vb + int(gridDim.x) < batch.total_tiles) {
-        stream_set_tile<kTN>(c, f, batch, c.vb + int(gridDim.x));
-    } else {
-        f.ga -= c.kstep_a; f.gb -= c.kstep_b;
-    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -449,32 +452,54 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
 
     // Fill stream.  Step g of the stream goes to stage g % 2.  Its loads are issued in two
     // halves: the first during the last quarter of step g - 2 (right after the barrier that
-    // frees the stage), the second during the first quarter of step g - 1.
+    // frees the stage), the second during the first quarter of step g - 1.  Both halves are
+    // issued from one position (cur, kt), which moves on in between: in the middle of a
+    // contraction step, without a branch (advance_0 .. advance_5 below).
     StreamPos pos;
-    Fill ahead2;                       // step g + 2 while step g is consumed: first half to issue
-    Fill ahead1;                       // step g + 1: second half to issue
     pos.pi = 0;
-    stream_set_tile<kTN>(pos, ahead1, batch, int(blockIdx.x));
-    {
-        FillRun run = fill_begin<0>(ahead1);
-        fill_range<0, kLoads>(ahead1, run, lds_wave_base);                   // step 0, all of it
-    }
-    stream_guess(pos, ahead1);
-    stream_settle<kTN>(pos, ahead1, batch);                                  // ahead1 = step 1
+    Run cur = stream_first<kTN>(pos, batch, int(blockIdx.x));
+    Run nxt;
+    stream_prepare<kTN>(pos, cur, nxt, batch);
+    int kt = 0;
+    bool sw = false;           // the position has just entered a new run
+
+    // (cur, kt) -> next step of the stream; in six parts so that each fits beside one MFMA.
+    // pick() takes values: a conditional expression over two variables is a choice between
+    // their addresses, which would keep them in memory.
+    auto advance_0 = [&]() {
+        ++kt;
+        sw = kt == cur.nk;
+        cur.ga = pick(sw, nxt.ga, cur.ga + step_bytes<kTN>(cur.ks_a));
+    };
+    auto advance_1 = [&]() { cur.ga2 = pick(sw, nxt.ga2, cur.ga2 + step_bytes<kTN>(cur.ks_a)); };
+    auto advance_2 = [&]() { cur.gb = pick(sw, nxt.gb, cur.gb + step_bytes<kTN>(cur.ks_b)); };
+    auto advance_3 = [&]() { cur.gb2 = pick(sw, nxt.gb2, cur.gb2 + step_bytes<kTN>(cur.ks_b)); };
+    auto advance_4 = [&]() {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) cur.va[p] = pick(sw, nxt.va[p], cur.va[p]);
+        if (kTN) {
+            cur.ks_a = pick(sw, nxt.ks_a, cur.ks_a);
+            cur.ks_b = pick(sw, nxt.ks_b, cur.ks_b);
+        }
+    };
+    auto advance_5 = [&]() {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) cur.vb[p] = pick(sw, nxt.vb[p], cur.vb[p]);
+        cur.nk = pick(sw, nxt.nk, cur.nk);
+        kt = pick(sw, 0, kt);
+    };
+    auto advance = [&]() { advance_0(); advance_1(); advance_2(); advance_3(); advance_4(); advance_5(); };
+
+    fill_range<0, kLoads>(cur, lds_wave_base);                               // step 0, all of it
+    advance();                                                               // step 1
+    if (sw) stream_prepare<kTN>(pos, cur, nxt, batch);
     wait_direct_loads();
     __syncthreads();
-    {
-        FillRun run = fill_begin<0>(ahead1);
-        fill_range<0, kLoadsStep3>(ahead1, run, lds_wave_base + kStageStride);   // step 1, first half
-    }
-    ahead2 = ahead1;
-    stream_guess(pos, ahead2);
-    stream_settle<kTN>(pos, ahead2, batch);                                  // ahead2 = step 2
+    fill_range<0, kLoadsStep3>(cur, lds_wave_base + kStageStride);           // its first half
 
     // The tile being consumed.
     int cvb = int(blockIdx.x);
     TilePos ct = locate_tile(batch, logical_tile(cvb, total), 0);
-    int cnk = tile_steps(batch, ct.pi);
 
     f32x16 acc[4][4];
     bf16x8 fa[2][4], fb[2][4];
@@ -483,17 +508,16 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) fb[0][j] = load_frag<kTN>(lds, fr.b[j], 0);
 
-    int g = 0;
+    uint32_t cur_off = 0;      // LDS byte offset of the stage being consumed: 0 or kStageStride
     // One contraction step of 64.  `first_tag` says whether it opens a tile: then its first
     // 16 MFMAs take a zero constant as their addend.
     auto contraction_step = [&](auto first_tag) {
         constexpr bool kFirst = decltype(first_tag)::value;
-        const int h = g & 1;
-        const char* cur = lds + h * kStageStride;
-        const char* nxt = lds + (1 - h) * kStageStride;
-        const uint32_t cur_fill = lds_wave_base + h * kStageStride;
-        const uint32_t nxt_fill = lds_wave_base + (1 - h) * kStageStride;
-        FillRun run;
+        const uint32_t nxt_off = cur_off ^ uint32_t(kStageStride);
+        const char* cur_stage = lds + cur_off;
+        const char* nxt_stage = lds + nxt_off;
+        const uint32_t cur_fill = lds_wave_base + cur_off;
+        const uint32_t nxt_fill = lds_wave_base + nxt_off;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         // Issue order below is pinned with scheduling fences.
         __builtin_amdgcn_sched_barrier(0);
@@ -507,7 +531,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
             }
-            const char* rd = s == 3 ? nxt : cur;     // step 3 reads step 0 of the next stage
+            const char* rd = s == 3 ? nxt_stage : cur_stage;     // step 3 reads step 0 of the next stage
             const int rs = s == 3 ? 0 : s + 1;
 #pragma unroll
             for (int q = 0; q < 16; ++q) {
@@ -524,21 +548,24 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
                 // The loads of one stage fill are spread over two quarters, so that the
                 // texture-address unit, which the waves share, is never asked for more than it
                 // can take while the matrix cores run: one load after every second MFMA.
-                if (s == 0 && q == 0) run = fill_begin<kLoadsStep3 / 2>(ahead1);
-                if (s == 3 && q == 0) run = fill_begin<0>(ahead2);
-                if (s == 0 && (q & 1)) {
+                if (s == 0 && (q & 1)) {                 // second half of the step after this one
                     switch (q >> 1) {
-#define TF_FILL_CASE(Q) case Q: fill_next<kLoadsStep3 + Q>(ahead1, run, nxt_fill); break;
+#define TF_FILL_CASE(Q) case Q: fill_next<kLoadsStep3 + Q>(cur, nxt_fill); break;
                         TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
                         TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
 #undef TF_FILL_CASE
                     }
                 }
-                // step g + 1 is on its way in full: what was two steps ahead is one step ahead now
-                if (s == 1 && q == 8) ahead1 = ahead2;
-                if (s == 3 && (q & 1)) {
+                // that step is on its way in full: move on to the one after it
+                if (s == 1 && q == 8) advance_0();
+                if (s == 1 && q == 9) advance_1();
+                if (s == 1 && q == 10) advance_2();
+                if (s == 1 && q == 11) advance_3();
+                if (s == 1 && q == 12) advance_4();
+                if (s == 1 && q == 13) advance_5();
+                if (s == 3 && (q & 1)) {                 // its first half, into the stage just freed
                     switch (q >> 1) {
-#define TF_FILL_CASE(Q) case Q: fill_next<Q>(ahead2, run, cur_fill); break;
+#define TF_FILL_CASE(Q) case Q: fill_next<Q>(cur, cur_fill); break;
                         TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
                         TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
 #undef TF_FILL_CASE
@@ -547,26 +574,33 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        stream_guess(pos, ahead2);
+        cur_off = nxt_off;
     };
 
-    // Tiles of this workgroup; the inner loop is the hot one and has a single taken branch
-    // per contraction step.
+    // Tiles of this workgroup; the inner loop is the hot one.  When the fill position has
+    // entered a new run during a step, the run after that one is worked out before the next
+    // step: the only decision in the loop, rarely taken, and taken on a counter of its own so
+    // that nothing inside a step depends on it.
+    int fill_left = cur.nk - kt;                   // steps until the fill position enters a new run
+    auto after_step = [&]() {
+        if (__builtin_expect(--fill_left == 0, 0)) {
+            stream_prepare<kTN>(pos, cur, nxt, batch);
+            fill_left = cur.nk;
+        }
+    };
     for (;;) {
+        const int cnk = tile_steps(batch, ct.pi);
         contraction_step(std::true_type{});
-        stream_settle<kTN>(pos, ahead2, batch);
-        ++g;
-        for (int kt = 1; kt < cnk; ++kt) {
+        after_step();
+        for (int k = 1; k < cnk; ++k) {
             contraction_step(std::false_type{});
-            stream_settle<kTN>(pos, ahead2, batch);
-            ++g;
+            after_step();
         }
         const GemmProblem& P = batch.p[ct.pi];
         store_block<kOutBf16, kAccumulate>(acc, wlds, P.C, P.N, ct.m0 + wm * 128, ct.n0 + wn * 128);
         cvb += stride;
         if (cvb >= total) break;
         ct = locate_tile(batch, logical_tile(cvb, total), ct.pi);
-        cnk = tile_steps(batch, ct.pi);
     }
     wait_direct_loads();      // nothing of this workgroup may still be in flight towards LDS
 }
@@ -601,7 +635,10 @@ int gemm_mfma_tile() { return kBM; }
 
 bool mfma_shape_ok(int64_t M, int64_t N, int64_t Kc, int64_t lda, int64_t ldb) {
     // 16-byte direct loads: row pitches must keep every row 16-byte aligned
-    return M > 0 && N > 0 && Kc > 0 && M % kBM == 0 && N % kBN == 0 && Kc % kBK == 0 && lda % 8 == 0 && ldb % 8 == 0;
+    // and 256 rows of either operand must lie within the 32-bit per-lane offsets of a stage fill
+    constexpr int64_t kMaxPitch = int64_t(1) << 22;
+    return M > 0 && N > 0 && Kc > 0 && M % kBM == 0 && N % kBN == 0 && Kc % kBK == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
+           lda <= kMaxPitch && ldb <= kMaxPitch;
 }
 
 hipError_t launch_gemm_mfma_bf16(hipStream_t stream, GemmBatch& batch, int n_problems,
