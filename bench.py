@@ -291,6 +291,34 @@ def main():
                     "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / PEAK_BF16_TFLOPS, "traffic": read_traffic("dx_mfma", cfg.cfg_id),
                     "avg_launch_ms": dx["avg_ms"], "flop_per_launch": fl}
+    if roofline and not args.no_sweep:
+        # The same launch on all-zero operands.  Data decides how far the chip can clock under its
+        # power limit: with nothing toggling in the matrix cores the clock stays near its maximum
+        # and the figure shows what the instruction stream itself delivers.  Context for `frac`,
+        # which is measured on the seeded inputs above.
+        zW = [torch.zeros_like(w) for w in st.W]
+        zdY = [torch.zeros_like(g) for g in st.dY]
+        all_frozen = np.ones(L, dtype=np.uint8)
+
+        def dx_only():
+            tf.tf_stage_backward(ctx, st.shapes, st.T, tf.TF_BF16, zW, st.X, zdY, all_frozen, st.dX, st.dW, tf.TF_BF16)
+
+        for _ in range(40):
+            dx_only()
+        torch.cuda.synchronize()
+        ctx.profile_enable(True)
+        ctx.profile_collect()
+        for _ in range(20):
+            dx_only()
+        torch.cuda.synchronize()
+        ms0 = [ms for k, ms in ctx.profile_collect() if k == "dx_mfma"]
+        ctx.profile_enable(False)
+        del zW, zdY
+        if ms0:
+            ach0 = 2.0 * T * P / (float(np.sum(ms0)) / 20 / 1e3) / 1e12
+            roofline["achieved_zero_operands"] = ach0
+            roofline["frac_zero_operands"] = ach0 / PEAK_BF16_TFLOPS
+            log(f"dX launch on all-zero operands: {ach0:.0f} TFLOP/s")
     extra = {}
     dw = head["kernels"].get("dw_mfma")
     if dw:

@@ -547,7 +547,8 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
                 }
                 // The loads of one stage fill are spread over two quarters, so that the
                 // texture-address unit, which the waves share, is never asked for more than it
-                // can take while the matrix cores run: one load after every second MFMA.
+                // can take while the matrix cores run: one load after every second MFMA (in the
+                // last quarter the even ones, which keeps the slot before the loop's back edge free).
                 if (s == 0 && (q & 1)) {                 // second half of the step after this one
                     switch (q >> 1) {
 #define TF_FILL_CASE(Q) case Q: fill_next<kLoadsStep3 + Q>(cur, nxt_fill); break;
@@ -563,7 +564,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
                 if (s == 1 && q == 11) advance_3();
                 if (s == 1 && q == 12) advance_4();
                 if (s == 1 && q == 13) advance_5();
-                if (s == 3 && (q & 1)) {                 // its first half, into the stage just freed
+                if (s == 3 && !(q & 1)) {                // its first half, into the stage just freed
                     switch (q >> 1) {
 #define TF_FILL_CASE(Q) case Q: fill_next<Q>(cur, cur_fill); break;
                         TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
