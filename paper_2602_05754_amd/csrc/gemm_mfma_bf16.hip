@@ -535,7 +535,9 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
             const int rs = s == 3 ? 0 : s + 1;
 #pragma unroll
             for (int q = 0; q < 16; ++q) {
-                const int i = q >> 2, j = q & 3;
+                // boustrophedon over the 4 x 4 tiles: consecutive MFMAs always share an operand
+                // (slightly less switching in the matrix cores, which the power limit pays back)
+                const int i = q >> 2, j = (i & 1) ? 3 - (q & 3) : (q & 3);
                 // D rows <- n (B operand rows), D columns <- m: a lane then owns 4 consecutive n
                 // of one output row m, i.e. 4 contiguous elements of row-major C.
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s & 1][j], fa[s & 1][i],
