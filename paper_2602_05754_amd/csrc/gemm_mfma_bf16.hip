@@ -42,19 +42,20 @@ namespace {
 constexpr int kBM = 256, kBN = 256, kBK = 64;
 constexpr int kWaves = 4, kThreads = 64 * kWaves;
 constexpr int kTileBytes = kBM * kBK * 2;             // 32 KB per operand per stage
-// LDS map: [A stage 0][A stage 1][B stage 0][B stage 1][epilogue areas].
-constexpr int kStageStride = kTileBytes;              // from stage 0 to stage 1 of one operand
-constexpr int kOperandB = 2 * kTileBytes;             // from operand A to operand B of one stage
-constexpr int kStagesBytes = 4 * kTileBytes;          // two stages of two operands = 128 KB
-constexpr int kEpiBytes = 8192;                       // per wave, beyond the stages
-constexpr int kLdsBytes = kStagesBytes + kWaves * kEpiBytes;   // 160 KB: all of a compute unit's LDS
+// LDS map: three stages of operand B (the "deep" one), two of operand A (the "shallow" one).
+// The third stage lets B's loads be issued almost two contraction steps before they are awaited,
+// and A's a whole step instead of half a one.  (Which operand is the deep one matters little:
+// measured on the two stage shapes, B was better by 1.4 % on one and worse by 0.4 % on the other.)
+// The epilogue borrows the deep stage that the tile's last step has just finished with.
+constexpr int kDeepStages = 3;
+constexpr int kShallowBase = kDeepStages * kTileBytes;            // shallow stages 0, 1 follow the deep ones
+constexpr int kEpiBytes = 8192;                                   // per wave, inside the borrowed stage
+constexpr int kLdsBytes = (kDeepStages + 2) * kTileBytes;         // 160 KB: all of a compute unit's LDS
+static_assert(kWaves * kEpiBytes == kTileBytes, "the four epilogue areas fill one stage");
 constexpr int kGroupM = 8;                            // tile rows per L2 locality group
 constexpr int kXcds = 8;
 constexpr int kXcdRun = 32;                           // consecutive logical tiles kept on one XCD
 constexpr int kLoads = 16;                            // 1 KB loads per wave and stage fill (8 per operand)
-// Loads of a stage fill issued in step 3 / in the next step 0.  Half and half measured
-// best; later loads arrive too late for the stage barrier.
-constexpr int kLoadsStep3 = kLoads / 2;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -124,58 +125,55 @@ __device__ __forceinline__ TilePos locate_tile(const GemmBatch& batch, int lt, i
 //   kTN: that KB is contraction rows T = 2 (4 p + w) + lane/32, 16-byte slot lane%32 of
 //        each; logical 64-byte block = physical block ^ (T & 3).
 // ---------------------------------------------------------------------------------------------
-struct Run {
-    // One contraction segment of one tile, as the fill stream sees it.  Loads p = 0..3 of an
-    // operand go through (ga, va[p]), loads 4..7 through (ga2, va[p - 4]).
-    const char* ga;           // wave-uniform global byte address: tile origin + contraction offset
-    const char* ga2;
-    const char* gb;
-    const char* gb2;
-    uint32_t ks_a, ks_b;      // byte advance per contraction step of 64 (kTN; a constant for kNT)
+struct Side {
+    // One operand of a run.  Loads p = 0..3 of a stage fill go through (g, v[p]), loads 4..7
+    // through (g2, v[p - 4]).
+    const char* g;            // wave-uniform global byte address: tile origin + contraction offset
+    const char* g2;
+    uint32_t ks;              // byte advance per contraction step of 64 (kTN; a constant for kNT)
+    uint32_t v[4];            // per-lane byte offsets; they depend on the row pitch only
+};
+struct Run {                  // one contraction segment of one tile, as the fill stream sees it
+    Side a, b;
     int nk;                   // steps of the segment
-    uint32_t va[4];           // per-lane byte offsets; they depend on the row pitch only
-    uint32_t vb[4];
 };
 
 template <bool kTN>
-__device__ __forceinline__ Run make_run(const GemmProblem& P, int m0, int n0) {
+__device__ __forceinline__ Side make_side(const uint16_t* base, int64_t ld, int origin) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int64_t lda = P.lda, ldb = P.ldb;
-    const uint16_t* A = static_cast<const uint16_t*>(P.A);
-    const uint16_t* B = static_cast<const uint16_t*>(P.B);
-    Run f;
-    f.nk = P.Kc / kBK;
+    Side f;
     if (kTN) {
         const int T = 2 * w + (lane >> 5);                     // + 8 p
         const int slot = lane & 31;
         const int blk = (slot >> 2) ^ (T & 3);
         const int col = blk * 32 + (slot & 3) * 8;             // element offset inside the 256-wide tile row
-        f.ga = reinterpret_cast<const char*>(A + m0);
-        f.gb = reinterpret_cast<const char*>(B + n0);
-        f.ga2 = f.ga + 8 * kWaves * lda * 2;
-        f.gb2 = f.gb + 8 * kWaves * ldb * 2;
+        f.g = reinterpret_cast<const char*>(base + origin);
+        f.g2 = f.g + 8 * kWaves * ld * 2;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            f.va[p] = uint32_t((int64_t(T + 2 * kWaves * p) * lda + col) * 2);
-            f.vb[p] = uint32_t((int64_t(T + 2 * kWaves * p) * ldb + col) * 2);
-        }
-        f.ks_a = uint32_t(kBK * lda * 2); f.ks_b = uint32_t(kBK * ldb * 2);
+        for (int p = 0; p < 4; ++p) f.v[p] = uint32_t((int64_t(T + 2 * kWaves * p) * ld + col) * 2);
+        f.ks = uint32_t(kBK * ld * 2);
     } else {
         const int r = 8 * w + (lane >> 3);                     // + 32 p
         const int pc = lane & 7;
-        f.ga = reinterpret_cast<const char*>(A + int64_t(m0) * lda);
-        f.gb = reinterpret_cast<const char*>(B + int64_t(n0) * ldb);
-        f.ga2 = f.ga + 32 * kWaves * lda * 2;
-        f.gb2 = f.gb + 32 * kWaves * ldb * 2;
+        f.g = reinterpret_cast<const char*>(base + int64_t(origin) * ld);
+        f.g2 = f.g + 32 * kWaves * ld * 2;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int R = r + 8 * kWaves * p;
             const int c = pc ^ ((R ^ (R >> 3)) & 7);           // the same for p and p + 4
-            f.va[p] = uint32_t((int64_t(R) * lda + c * 8) * 2);
-            f.vb[p] = uint32_t((int64_t(R) * ldb + c * 8) * 2);
+            f.v[p] = uint32_t((int64_t(R) * ld + c * 8) * 2);
         }
-        f.ks_a = f.ks_b = 0;
+        f.ks = 0;
     }
+    return f;
+}
+
+template <bool kTN>
+__device__ __forceinline__ Run make_run(const GemmProblem& P, int m0, int n0) {
+    Run f;
+    f.a = make_side<kTN>(static_cast<const uint16_t*>(P.A), P.lda, m0);
+    f.b = make_side<kTN>(static_cast<const uint16_t*>(P.B), P.ldb, n0);
+    f.nk = P.Kc / kBK;
     return f;
 }
 
@@ -200,28 +198,18 @@ __device__ __forceinline__ void wait_direct_loads() {
     __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0), other counters untouched
 }
 
-// Issue load number q (0 .. kLoads-1) of a stage fill (load p of an operand fetches KB number
-// 4 p + w of its tile).  kTN: even q fetch operand A, odd q operand B, p = q / 2.  kNT: the first
-// eight are operand A, the last eight operand B - the half of a fill that is issued first has twice
-// as long to arrive, and in an input gradient A (the output gradients, read once) comes from HBM
-// while B (the weights, shared by every row of tiles) is mostly found in a cache (measured: +2 % on
-// the 8B stage, +0.4 % on the 1B stage; for kTN operand-first orders were 0 to -0.7 %).
-// lds_wave_base is the LDS byte address of the stage (of operand A) plus 1 KB times the wave
-// index.  Nothing but the load itself: every address is ready in a register.
-template <bool kTN, int q>
-__device__ __forceinline__ void fill_next(const Run& f, uint32_t lds_wave_base) {
-    constexpr int p = kTN ? q >> 1 : q & 7;
-    constexpr bool kIsA = kTN ? (q & 1) == 0 : q < kLoads / 2;
-    constexpr int kOff = p * kWaves * 1024;
-    if (kIsA) direct_load_16B<kOff>(p < 4 ? f.ga : f.ga2, f.va[p & 3], lds_wave_base);
-    else      direct_load_16B<kOperandB + kOff>(p < 4 ? f.gb : f.gb2, f.vb[p & 3], lds_wave_base);
+// Load p (0..7) of one operand's stage fill: it fetches KB number 4 p + w of the 32 KB stage.
+// lds_stage is the LDS byte address of the stage plus 1 KB times the wave index.  Nothing but
+// the load itself: every address is ready in a register.
+template <int p>
+__device__ __forceinline__ void fill_load(const char* g, const char* g2, const uint32_t (&v)[4], uint32_t lds_stage) {
+    direct_load_16B<p * kWaves * 1024>(p < 4 ? g : g2, v[p & 3], lds_stage);
 }
-
-template <bool kTN, int q, int end>
-__device__ __forceinline__ void fill_range(const Run& f, uint32_t lds_wave_base) {
-    if constexpr (q < end) {
-        fill_next<kTN, q>(f, lds_wave_base);
-        fill_range<kTN, q + 1, end>(f, lds_wave_base);
+template <int p, int end>
+__device__ __forceinline__ void fill_side(const Side& f, uint32_t lds_stage) {
+    if constexpr (p < end) {
+        fill_load<p>(f.g, f.g2, f.v, lds_stage);
+        fill_side<p + 1, end>(f, lds_stage);
     }
 }
 
@@ -262,14 +250,14 @@ __device__ __forceinline__ void stream_prepare(StreamPos& c, const Run& cur, Run
     } else if (c.vb + int(gridDim.x) < batch.total_tiles) {
         nxt = stream_first<kTN>(c, batch, c.vb + int(gridDim.x));
     } else {
-        const int64_t last_a = int64_t(cur.nk - 1) * step_bytes<kTN>(cur.ks_a);
-        const int64_t last_b = int64_t(cur.nk - 1) * step_bytes<kTN>(cur.ks_b);
-        nxt.ga = cur.ga + last_a; nxt.ga2 = cur.ga2 + last_a;
-        nxt.gb = cur.gb + last_b; nxt.gb2 = cur.gb2 + last_b;
-        nxt.ks_a = cur.ks_a; nxt.ks_b = cur.ks_b;
+        const int64_t last_a = int64_t(cur.nk - 1) * step_bytes<kTN>(cur.a.ks);
+        const int64_t last_b = int64_t(cur.nk - 1) * step_bytes<kTN>(cur.b.ks);
+        nxt.a.g = cur.a.g + last_a; nxt.a.g2 = cur.a.g2 + last_a;
+        nxt.b.g = cur.b.g + last_b; nxt.b.g2 = cur.b.g2 + last_b;
+        nxt.a.ks = cur.a.ks; nxt.b.ks = cur.b.ks;
         nxt.nk = 1;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) { nxt.va[p] = cur.va[p]; nxt.vb[p] = cur.vb[p]; }
+        for (int p = 0; p < 4; ++p) { nxt.a.v[p] = cur.a.v[p]; nxt.b.v[p] = cur.b.v[p]; }
     }
 }
 
@@ -286,7 +274,7 @@ __device__ __forceinline__ int tile_steps(const GemmBatch& batch, int pi) {
 // Operand lane l holds row (l % 32) of a 32-row block and contraction values 8 (l / 32) .. + 7.
 // ---------------------------------------------------------------------------------------------
 struct FragAddr {
-    int a[4], b[4];     // per-lane LDS byte offsets (stage 0) of the row blocks, step 0
+    int a[4], b[4];     // per-lane LDS byte offsets of the row blocks inside a stage of their operand, step 0
 };
 
 template <bool kTN>
@@ -303,7 +291,7 @@ __device__ __forceinline__ FragAddr make_frag_addr(int wm, int wn) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) fa.a[i] = laneoff + (((wm * 4 + i) ^ x) * 64);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fa.b[j] = kOperandB + laneoff + (((wn * 4 + j) ^ x) * 64);
+        for (int j = 0; j < 4; ++j) fa.b[j] = laneoff + (((wn * 4 + j) ^ x) * 64);
     } else {
         const int lrow = lane & 31, lhalf = lane >> 5;
         // chunk (2 s + lhalf) ^ swz(row): the s-dependent part is XORed in at use
@@ -315,7 +303,7 @@ __device__ __forceinline__ FragAddr make_frag_addr(int wm, int wn) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int rb = wn * 128 + j * 32 + lrow;
-            fa.b[j] = kOperandB + rb * 128 + ((lhalf ^ ((rb ^ (rb >> 3)) & 7)) << 4);
+            fa.b[j] = rb * 128 + ((lhalf ^ ((rb ^ (rb >> 3)) & 7)) << 4);
         }
     }
     return fa;
@@ -452,14 +440,18 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     // plus this wave's 1 KB slot inside every group of 4 KB of a stage fill.
     const uint32_t lds_wave_base = __builtin_amdgcn_readfirstlane(
         uint32_t(reinterpret_cast<uintptr_t>(TF_LPTR(lds))) + uint32_t(wave) * 1024u);
-    char* wlds = lds + kStagesBytes + wave * kEpiBytes;
     const FragAddr fr = make_frag_addr<kTN>(wm, wn);
 
-    // Fill stream.  Step g of the stream goes to stage g % 2.  Its loads are issued in two
-    // halves: the first during the last quarter of step g - 2 (right after the barrier that
-    // frees the stage), the second during the first quarter of step g - 1.  Both halves are
-    // issued from one position (cur, kt), which moves on in between: in the middle of a
-    // contraction step, without a branch (advance_0 .. advance_5 below).
+    // Fill stream.  The deep operand (B) of step g goes to deep stage g % 3, the shallow operand
+    // (A) to shallow stage g % 2.  During step g the loads of the deep operand
+    // of step g + 2 are issued in the first quarter (their stage was freed by the barrier of
+    // step g - 1) and those of the shallow operand of step g + 2 in the last quarter, right
+    // after the barrier that frees its stage.  The barrier of step g needs both operands of step
+    // g + 1: everything but the eight youngest loads (the deep operand of step g + 2).  So the
+    // deep operand has 1 3/4 steps to arrive and the shallow one a whole step.
+    // Both are issued from one position (cur, kt): the deep loads read it directly, then a copy
+    // of its shallow side is kept (`lag`) and the position moves on, in the middle of the step,
+    // without a branch (advance_0 .. advance_6 below).
     StreamPos pos;
     pos.pi = 0;
     Run cur = stream_first<kTN>(pos, batch, int(blockIdx.x));
@@ -467,76 +459,118 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     stream_prepare<kTN>(pos, cur, nxt, batch);
     int kt = 0;
     bool sw = false;           // the position has just entered a new run
+    Side lag;                  // shallow side of the step before the one `cur` stands on
 
-    // (cur, kt) -> next step of the stream; in six parts so that each fits beside one MFMA.
+    auto deep = [](Run& r) -> Side& { return r.b; };
+    auto shallow = [](Run& r) -> Side& { return r.a; };
+
+    // (cur, kt) -> next step of the stream; in parts so that each fits beside one MFMA.
     // pick() takes values: a conditional expression over two variables is a choice between
     // their addresses, which would keep them in memory.
+    // (the copies are written out so that they stay where they are put: as plain assignments the
+    // compiler moves them to the top of the step, into the one slot that has no room)
+    auto keep_lag = [&]() {
+        const Side& sh = shallow(cur);
+        asm volatile("s_mov_b64 %0, %1" : "=s"(lag.g) : "s"(sh.g));
+        asm volatile("s_mov_b64 %0, %1" : "=s"(lag.g2) : "s"(sh.g2));
+#pragma unroll
+        for (int p = 0; p < 4; ++p) asm volatile("v_mov_b32 %0, %1" : "=v"(lag.v[p]) : "v"(sh.v[p]));
+    };
     auto advance_0 = [&]() {
         ++kt;
         sw = kt == cur.nk;
-        cur.ga = pick(sw, nxt.ga, cur.ga + step_bytes<kTN>(cur.ks_a));
+        cur.a.g = pick(sw, nxt.a.g, cur.a.g + step_bytes<kTN>(cur.a.ks));
     };
-    auto advance_1 = [&]() { cur.ga2 = pick(sw, nxt.ga2, cur.ga2 + step_bytes<kTN>(cur.ks_a)); };
-    auto advance_2 = [&]() { cur.gb = pick(sw, nxt.gb, cur.gb + step_bytes<kTN>(cur.ks_b)); };
-    auto advance_3 = [&]() { cur.gb2 = pick(sw, nxt.gb2, cur.gb2 + step_bytes<kTN>(cur.ks_b)); };
+    auto advance_1 = [&]() { cur.a.g2 = pick(sw, nxt.a.g2, cur.a.g2 + step_bytes<kTN>(cur.a.ks)); };
+    auto advance_2 = [&]() { cur.b.g = pick(sw, nxt.b.g, cur.b.g + step_bytes<kTN>(cur.b.ks)); };
+    auto advance_3 = [&]() { cur.b.g2 = pick(sw, nxt.b.g2, cur.b.g2 + step_bytes<kTN>(cur.b.ks)); };
     auto advance_4 = [&]() {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) cur.va[p] = pick(sw, nxt.va[p], cur.va[p]);
+        for (int p = 0; p < 4; ++p) cur.a.v[p] = pick(sw, nxt.a.v[p], cur.a.v[p]);
         if (kTN) {
-            cur.ks_a = pick(sw, nxt.ks_a, cur.ks_a);
-            cur.ks_b = pick(sw, nxt.ks_b, cur.ks_b);
+            cur.a.ks = pick(sw, nxt.a.ks, cur.a.ks);
+            cur.b.ks = pick(sw, nxt.b.ks, cur.b.ks);
         }
     };
     auto advance_5 = [&]() {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) cur.vb[p] = pick(sw, nxt.vb[p], cur.vb[p]);
+        for (int p = 0; p < 4; ++p) cur.b.v[p] = pick(sw, nxt.b.v[p], cur.b.v[p]);
         cur.nk = pick(sw, nxt.nk, cur.nk);
         kt = pick(sw, 0, kt);
     };
     auto advance = [&]() { advance_0(); advance_1(); advance_2(); advance_3(); advance_4(); advance_5(); };
 
-    fill_range<kTN, 0, kLoads>(cur, lds_wave_base);                               // step 0, all of it
-    advance();                                                               // step 1
+    // Steps 0 and 1 in full; the position ends on step 2.
+    fill_side<0, 8>(deep(cur), lds_wave_base);
+    fill_side<0, 8>(shallow(cur), lds_wave_base + kShallowBase);
+    advance();
     if (sw) stream_prepare<kTN>(pos, cur, nxt, batch);
-    wait_direct_loads();
+    fill_side<0, 8>(deep(cur), lds_wave_base + kTileBytes);
+    fill_side<0, 8>(shallow(cur), lds_wave_base + kShallowBase + kTileBytes);
+    advance();
+    if (sw) stream_prepare<kTN>(pos, cur, nxt, batch);
+    __builtin_amdgcn_s_waitcnt(0x4f70);        // vmcnt(16): step 0 has landed
     __syncthreads();
-    fill_range<kTN, 0, kLoadsStep3>(cur, lds_wave_base + kStageStride);           // its first half
 
     // The tile being consumed.
     int cvb = int(blockIdx.x);
     TilePos ct = locate_tile(batch, logical_tile(cvb, total), 0);
 
+    // Stage offsets (bytes from the start of LDS): d0 / s0 hold the step being consumed, d1 / s1
+    // the next one, d2 is the deep stage that this step's first quarter fills.
+    uint32_t d0 = 0, d1 = kTileBytes, d2 = 2 * kTileBytes;
+    uint32_t s0 = kShallowBase, s1 = kShallowBase + kTileBytes;
+    auto stage_a = [&](uint32_t d, uint32_t sh) { return lds + sh; };
+    auto stage_b = [&](uint32_t d, uint32_t sh) { return lds + d; };
+
     f32x16 acc[4][4];
     bf16x8 fa[2][4], fb[2][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fa[0][i] = load_frag<kTN>(lds, fr.a[i], 0);
+    for (int i = 0; i < 4; ++i) fa[0][i] = load_frag<kTN>(stage_a(d0, s0), fr.a[i], 0);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) fb[0][j] = load_frag<kTN>(lds, fr.b[j], 0);
+    for (int j = 0; j < 4; ++j) fb[0][j] = load_frag<kTN>(stage_b(d0, s0), fr.b[j], 0);
 
-    uint32_t cur_off = 0;      // LDS byte offset of the stage being consumed: 0 or kStageStride
+    // Stage offsets of the next step (written out for the same reason as keep_lag).
+    auto rotate_deep = [&]() {
+        uint32_t t;
+        asm volatile("s_mov_b32 %0, %1" : "=s"(t) : "s"(d0));
+        asm volatile("s_mov_b32 %0, %1" : "=s"(d0) : "s"(d1));
+        asm volatile("s_mov_b32 %0, %1" : "=s"(d1) : "s"(d2));
+        asm volatile("s_mov_b32 %0, %1" : "=s"(d2) : "s"(t));
+    };
+    auto rotate_shallow = [&]() {
+        uint32_t t;
+        asm volatile("s_mov_b32 %0, %1" : "=s"(t) : "s"(s0));
+        asm volatile("s_mov_b32 %0, %1" : "=s"(s0) : "s"(s1));
+        asm volatile("s_mov_b32 %0, %1" : "=s"(s1) : "s"(t));
+    };
+
     // One contraction step of 64.  `first_tag` says whether it opens a tile: then its first
     // 16 MFMAs take a zero constant as their addend.
     auto contraction_step = [&](auto first_tag) {
         constexpr bool kFirst = decltype(first_tag)::value;
-        const uint32_t nxt_off = cur_off ^ uint32_t(kStageStride);
-        const char* cur_stage = lds + cur_off;
-        const char* nxt_stage = lds + nxt_off;
-        const uint32_t cur_fill = lds_wave_base + cur_off;
-        const uint32_t nxt_fill = lds_wave_base + nxt_off;
+        const char* cur_a = stage_a(d0, s0);
+        const char* cur_b = stage_b(d0, s0);
+        const char* nxt_a = stage_a(d1, s1);
+        const char* nxt_b = stage_b(d1, s1);
+        const uint32_t deep_fill = lds_wave_base + d2;
+        const uint32_t shallow_fill = lds_wave_base + s0;
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         // Issue order below is pinned with scheduling fences.
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             if (s == 3) {
-                // every operand read of this stage has been issued: wait for them and for this
-                // wave's part of the next stage, then meet the other waves.  After the barrier
-                // the next stage is complete and this one may be overwritten.
-                wait_direct_loads();
+                // every operand read of this step's stages has been issued: wait for them and for
+                // this wave's part of the next step (all loads but the eight issued in the first
+                // quarter), then meet the other waves.  After the barrier the next step's stages
+                // are complete and this step's may be overwritten.
+                __builtin_amdgcn_s_waitcnt(0x0f78);     // vmcnt(8), other counters untouched
                 __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
             }
-            const char* rd = s == 3 ? nxt_stage : cur_stage;     // step 3 reads step 0 of the next stage
+            const char* rd_a = s == 3 ? nxt_a : cur_a;     // quarter 3 reads quarter 0 of the next step
+            const char* rd_b = s == 3 ? nxt_b : cur_b;
             const int rs = s == 3 ? 0 : s + 1;
 #pragma unroll
             for (int q = 0; q < 16; ++q) {
@@ -549,31 +583,32 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
                                                                    (kFirst && s == 0) ? zero : acc[i][j], 0, 0, 0);
                 if (q < 8) {
                     // operand order A0 B0 A1 B1 A2 B2 A3 B3
-                    if (q & 1) fb[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.b[q >> 1], rs);
-                    else       fa[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd, fr.a[q >> 1], rs);
+                    if (q & 1) fb[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd_b, fr.b[q >> 1], rs);
+                    else       fa[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd_a, fr.a[q >> 1], rs);
                 }
-                // The loads of one stage fill are spread over two quarters, so that the
-                // texture-address unit, which the waves share, is never asked for more than it
-                // can take while the matrix cores run: one load after every second MFMA (in the
-                // last quarter the even ones, which keeps the slot before the loop's back edge free).
-                if (s == 0 && (q & 1)) {                 // second half of the step after this one
+                // One load after every second MFMA: the texture-address unit, which the waves
+                // share, is then never asked for more than it can take while the matrix cores run.
+                if (s == 0 && (q & 1)) {                 // deep operand of the step after the next
                     switch (q >> 1) {
-#define TF_FILL_CASE(Q) case Q: fill_next<kTN, kLoadsStep3 + Q>(cur, nxt_fill); break;
+#define TF_FILL_CASE(Q) case Q: fill_load<Q>(deep(cur).g, deep(cur).g2, deep(cur).v, deep_fill); break;
                         TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
                         TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
 #undef TF_FILL_CASE
                     }
                 }
-                // that step is on its way in full: move on to the one after it
+                // its shallow operand follows in the last quarter; until then the position moves on
+                if (s == 0 && q == 14) keep_lag();
                 if (s == 1 && q == 8) advance_0();
                 if (s == 1 && q == 9) advance_1();
                 if (s == 1 && q == 10) advance_2();
                 if (s == 1 && q == 11) advance_3();
                 if (s == 1 && q == 12) advance_4();
                 if (s == 1 && q == 13) advance_5();
-                if (s == 3 && !(q & 1)) {                // its first half, into the stage just freed
+                if (s == 2 && q == 12) rotate_deep();     // the step itself works on copies taken at its top
+                if (s == 2 && q == 13) rotate_shallow();
+                if (s == 3 && !(q & 1)) {                // (the even slots: the last one stays free for the loop's back edge)
                     switch (q >> 1) {
-#define TF_FILL_CASE(Q) case Q: fill_next<kTN, Q>(cur, cur_fill); break;
+#define TF_FILL_CASE(Q) case Q: fill_load<Q>(lag.g, lag.g2, lag.v, shallow_fill); break;
                         TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
                         TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
 #undef TF_FILL_CASE
@@ -582,7 +617,6 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        cur_off = nxt_off;
     };
 
     // Tiles of this workgroup; the inner loop is the hot one.  When the fill position has
@@ -604,10 +638,13 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
             contraction_step(std::false_type{});
             after_step();
         }
+        // The deep stage that the last step consumed (d2 after the rotation) is the epilogue's:
+        // every wave is past that step's barrier, and its next fill is issued by the next step.
         const GemmProblem& P = batch.p[ct.pi];
-        store_block<kOutBf16, kAccumulate>(acc, wlds, P.C, P.N, ct.m0 + wm * 128, ct.n0 + wn * 128);
+        store_block<kOutBf16, kAccumulate>(acc, lds + d2 + wave * kEpiBytes, P.C, P.N, ct.m0 + wm * 128, ct.n0 + wn * 128);
         cvb += stride;
         if (cvb >= total) break;
+        __syncthreads();          // no wave may fill that stage while another still turns its block around in it
         ct = locate_tile(batch, logical_tile(cvb, total), ct.pi);
     }
     wait_direct_loads();      // nothing of this workgroup may still be in flight towards LDS
