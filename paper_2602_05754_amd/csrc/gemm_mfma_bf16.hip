@@ -8,18 +8,21 @@
 // Persistent workgroups: one per compute unit, each walking every gridDim.x-th
 // 256 x 256 output tile of the launch.  Four waves in a 2 x 2 grid, 128 x 128 per
 // wave = 4 x 4 MFMA 32x32x16 tiles, 256 accumulators per lane.  The contraction
-// advances 64 at a time through two LDS stages of 64 KB that are filled by direct
-// global->LDS loads (no register staging).  The fills form ONE stream over all
-// tiles of the workgroup: while the matrix cores finish a tile, the first two
-// contraction steps of the next tile are already in flight, so a tile switch costs
-// the epilogue and nothing else - no drain, no refill, no new workgroup.
+// advances 64 at a time through LDS stages of 32 KB per operand - two for A, three
+// for B, all of the 160 KB - that are filled by direct global->LDS loads (no
+// register staging): A's loads are issued one contraction step before they are
+// awaited, B's 1 3/4 steps.  The fills form ONE stream over all tiles of the
+// workgroup: while the matrix cores finish a tile, the first two contraction steps
+// of the next tile are already in flight, so a tile switch costs the epilogue and
+// nothing else - no drain, no refill, no new workgroup.
 // A stage is consumed in four steps of 16; the operands of step s + 1 are read
 // from LDS while the MFMAs of step s issue, the stage barrier sits after the reads
 // of the last step, and the first operands of the next stage are read during the
 // last step, so neither LDS latency nor the barrier leaves the matrix cores idle.
 // The first step of a tile multiplies into a zero constant instead of clearing
-// 256 registers.  The epilogue turns 32-row blocks around in 8 KB of LDS per wave
-// that lies beyond the two stages, so it never collides with the fills in flight.
+// 256 registers.  The epilogue turns 32-row blocks around in 8 KB of LDS per wave,
+// inside the B stage that the tile's last step has finished with and that is filled
+// again only by the next step (a barrier after the epilogue keeps it that way).
 // A problem may name which 256-row blocks of its output exist (row_bits: frozen row
 // blocks of a weight gradient have no tiles) and may continue its contraction over
 // the descriptors that follow it (n_seg: layers that share their input give one
