@@ -62,7 +62,7 @@ constexpr int kLoads = 16;                            // 1 KB loads per wave and
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t U2 __attribute__((ext_vector_type(2)));
 typedef uint32_t U4 __attribute__((ext_vector_type(4)));
 typedef float F4 __attribute__((ext_vector_type(4)));
@@ -147,13 +147,18 @@ __device__ __forceinline__ Side make_side(const uint16_t* base, int64_t ld, int 
     Side f;
     if (kTN) {
         const int T = 2 * w + (lane >> 5);                     // + 8 p
-        const int slot = lane & 31;
-        const int blk = (slot >> 2) ^ (T & 3);
-        const int col = blk * 32 + (slot & 3) * 8;             // element offset inside the 256-wide tile row
+        const int slot = lane & 31;                            // 16-byte unit of the 512-byte row
+        // logical 32-byte unit = physical unit ^ f(T), f(T) = 4 ((T / 8) % 4) + T % 4: adding 8 p to T
+        // changes (T / 8) % 4 by p % 4, which is folded in below
+        const int col = 0;                                     // (worked out per p)
         f.g = reinterpret_cast<const char*>(base + origin);
         f.g2 = f.g + 8 * kWaves * ld * 2;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) f.v[p] = uint32_t((int64_t(T + 2 * kWaves * p) * ld + col) * 2);
+        for (int p = 0; p < 4; ++p) {
+            const int Tp = T + 2 * kWaves * p;                 // loads p and p + 4 differ by 32 rows: the same f
+            const int unit = (slot >> 1) ^ (4 * ((Tp >> 3) & 3) + (Tp & 3));
+            f.v[p] = uint32_t((int64_t(Tp) * ld + unit * 16 + (slot & 1) * 8 + col) * 2);
+        }
         f.ks = uint32_t(kBK * ld * 2);
     } else {
         const int r = 8 * w + (lane >> 3);                     // + 32 p
@@ -273,11 +278,14 @@ __device__ __forceinline__ int tile_steps(const GemmBatch& batch, int pi) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// MFMA operand fetch for contraction step s (16 values) of the current stage.
-// Operand lane l holds row (l % 32) of a 32-row block and contraction values 8 (l / 32) .. + 7.
+// MFMA operand fetch.  The MFMA is v_mfma_f32_16x16x32_bf16 (measured from registers with random
+// operands, where the chip's power limit decides: 15 % more sustained than the 32x32x16 form, whose
+// accumulator traffic per FLOP is twice as large).  Operand lane l holds row (l % 16) of a 16-row
+// block and contraction values 8 (l / 16) .. + 7 of the 32 that one instruction contracts; a stage
+// holds two such sub-steps u = 0, 1.
 // ---------------------------------------------------------------------------------------------
 struct FragAddr {
-    int a[4], b[4];     // per-lane LDS byte offsets of the row blocks inside a stage of their operand, step 0
+    int a[8], b[8];     // per-lane LDS byte offsets of the 16-row blocks inside a stage of their operand, sub-step 0
 };
 
 template <bool kTN>
@@ -285,87 +293,91 @@ __device__ __forceinline__ FragAddr make_frag_addr(int wm, int wn) {
     const int lane = threadIdx.x & 63;
     FragAddr fa;
     if (kTN) {
-        // 16-lane group G reads rows 8 (G / 2) + {0..3} (+4 for the second read) of the
-        // contraction and columns 16 (G % 2) + {0..15} of the 32-row block; as a source lane
-        // ii of its group it fetches row ii / 4, columns 4 (ii % 4) .. + 3.
+        // LDS transpose read (ds_read_b64_tr_b16): within 16 lanes, result lane i element e comes
+        // from source lane 4 e + i / 4, element i % 4.  Lane group G = l / 16 needs contraction rows
+        // 8 G .. + 3 (second read: + 4) of the 16 tile rows of its block; as source lane ii it
+        // fetches contraction row 8 G + ii / 4, tile rows 4 (ii % 4) .. + 3 (8 bytes).  That row's
+        // 32-byte units are XOR-swizzled with 4 G + ii / 4 (make_side), which is different for all
+        // 16 rows that one instruction touches: no bank conflicts.
         const int G = lane >> 4, ii = lane & 15;
         const int x = ii >> 2;
-        const int laneoff = (8 * (G >> 1) + x) * 512 + 32 * (G & 1) + 8 * (ii & 3);
+        const int laneoff = (8 * G + x) * 512 + 8 * (ii & 3);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) fa.a[i] = laneoff + (((wm * 4 + i) ^ x) * 64);
+        for (int i = 0; i < 8; ++i) fa.a[i] = laneoff + (((wm * 8 + i) ^ (4 * G + x)) * 32);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fa.b[j] = laneoff + (((wn * 4 + j) ^ x) * 64);
+        for (int j = 0; j < 8; ++j) fa.b[j] = laneoff + (((wn * 8 + j) ^ (4 * G + x)) * 32);
     } else {
-        const int lrow = lane & 31, lhalf = lane >> 5;
-        // chunk (2 s + lhalf) ^ swz(row): the s-dependent part is XORed in at use
+        const int lrow = lane & 15, lq = lane >> 4;
+        // chunk (4 u + lq) ^ swz(row): the u-dependent part is XORed in at use
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int ra = wm * 128 + i * 32 + lrow;
-            fa.a[i] = ra * 128 + ((lhalf ^ ((ra ^ (ra >> 3)) & 7)) << 4);
+        for (int i = 0; i < 8; ++i) {
+            const int ra = wm * 128 + i * 16 + lrow;
+            fa.a[i] = ra * 128 + ((lq ^ ((ra ^ (ra >> 3)) & 7)) << 4);
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int rb = wn * 128 + j * 32 + lrow;
-            fa.b[j] = rb * 128 + ((lhalf ^ ((rb ^ (rb >> 3)) & 7)) << 4);
+        for (int j = 0; j < 8; ++j) {
+            const int rb = wn * 128 + j * 16 + lrow;
+            fa.b[j] = rb * 128 + ((lq ^ ((rb ^ (rb >> 3)) & 7)) << 4);
         }
     }
     return fa;
 }
 
 template <bool kTN>
-__device__ __forceinline__ bf16x8 load_frag(const char* stage, int addr, int s) {
+__device__ __forceinline__ bf16x8 load_frag(const char* stage, int addr, int u) {
     if (kTN) {
         const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-            (LdsBf16x4Ptr)TF_LPTR(stage + addr + (16 * s) * 512));
+            (LdsBf16x4Ptr)TF_LPTR(stage + addr + (32 * u) * 512));
         const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(
-            (LdsBf16x4Ptr)TF_LPTR(stage + addr + (16 * s + 4) * 512));
+            (LdsBf16x4Ptr)TF_LPTR(stage + addr + (32 * u + 4) * 512));
         return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
     } else {
-        // chunk index 2 s + lhalf, swizzled: 2 s only touches bits 1..2 of the chunk, lhalf bit 0
-        return *reinterpret_cast<const bf16x8*>(stage + (addr ^ (s << 5)));
+        // chunk index 4 u + lq, swizzled: 4 u only touches bit 2 of the chunk, lq bits 0..1
+        return *reinterpret_cast<const bf16x8*>(stage + (addr ^ (u << 6)));
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Epilogue of one tile, per wave: acc[i][j][4g + e] is C[m][n] with
-//   m = row0 + i*32 + lane%32,  n = col0 + j*32 + 8g + 4*(lane/32) + e.
+// Epilogue of one tile, per wave: acc[i][j][e] is C[m][n] with
+//   m = row0 + 16 i + lane % 16,  n = col0 + 16 j + 4 (lane / 16) + e.
 // A lane's values are scattered over the block, so the wave turns 8 KB pieces around in its
 // own LDS area `wlds` (32 rows of 256 bytes) and writes whole 256-byte row segments.
 // ---------------------------------------------------------------------------------------------
-template <bool kOutBf16, bool kAccumulate>
-__device__ __forceinline__ void store_block(const f32x16 (&acc)[4][4], char* wlds, void* C, int64_t N,
+template <bool kOutBf16, bool kAccumulate, int kAhead>
+__device__ __forceinline__ void store_block(const f32x4 (&acc)[8][8], char* wlds, void* C, int64_t N,
                                             int row0, int col0) {
     int lane = threadIdx.x & 63;
     // The epilogue sits inside the tile loop.  Its per-lane addresses are loop invariants, and
     // kept in registers across the contraction steps they would crowd out the operands: make
     // the lane number opaque so that they are worked out again for every tile instead.
     asm volatile("" : "+v"(lane));
-    const int lrow = lane & 31, lhalf = lane >> 5;
+    const int lrow = lane & 15, lq = lane >> 4;
     const int cb = lane & 15, rsub = lane >> 4;        // 16-byte column block, row inside a group of 4
     if (kOutBf16) {
-        // One pass per 32-row block: [32 rows][32 chunks of 8 bytes]; the chunk index is XORed
-        // with the row so that the 32 rows written by one instruction fall into different banks.
+        // One pass per 32-row block (two 16-row blocks of accumulators): [32 rows][32 chunks of
+        // 8 bytes]; the chunk index is XORed with the row so that the rows written by one
+        // instruction fall into different banks.
         // Software pipeline: the accumulators of pass i + 1 are read and rounded in between the
         // global stores of pass i, whose rate (the four waves share one path to memory) sets the
         // pace.  The stores are non-temporal: the output is not read again by this kernel, and
         // left in L2 it would push out the operand panels that the other workgroups still fetch.
         uint16_t* Cw = static_cast<uint16_t*>(C) + int64_t(row0) * N + col0 + cb * 8;
-        U2 pk[16];                         // one pass, rounded: pk[4 j + g] is chunk 8 j + 2 g + lhalf of row lrow
-        auto round_piece = [&](int i, int k) {      // two of the sixteen chunks of pass i
+        U2 pk[16];                         // one pass, rounded: pk[8 h + j] is chunk 4 j + lq of row 16 h + lrow
+        auto round_piece = [&](int ps, int k) {     // two of the sixteen chunks of pass ps
 #pragma unroll
             for (int gg = 0; gg < 2; ++gg) {
-                const int j = k >> 1, g = (k & 1) * 2 + gg;
-                pk[4 * j + g] = U2{f32x2_to_bf16x2(acc_read(acc[i][j][4 * g + 0]), acc_read(acc[i][j][4 * g + 1])),
-                                   f32x2_to_bf16x2(acc_read(acc[i][j][4 * g + 2]), acc_read(acc[i][j][4 * g + 3]))};
+                const int q = 2 * k + gg, h = q >> 3, j = q & 7;
+                const f32x4& a = acc[2 * ps + h][j];
+                pk[q] = U2{f32x2_to_bf16x2(acc_read(a[0]), acc_read(a[1])), f32x2_to_bf16x2(acc_read(a[2]), acc_read(a[3]))};
             }
         };
         auto to_lds = [&]() {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int c = 8 * j + 2 * g + lhalf;
-                    *reinterpret_cast<U2*>(wlds + lrow * 256 + ((c ^ lrow) << 3)) = pk[4 * j + g];
+                for (int j = 0; j < 8; ++j) {
+                    const int c = 4 * j + lq, r = 16 * h + lrow;
+                    *reinterpret_cast<U2*>(wlds + r * 256 + ((c ^ r) << 3)) = pk[8 * h + j];
                 }
         };
         __builtin_amdgcn_sched_barrier(0);
@@ -395,36 +407,39 @@ __device__ __forceinline__ void store_block(const f32x16 (&acc)[4][4], char* wld
         }
     } else {
         // fp32: one pass per 32 rows x 64 columns: [32 rows][16 chunks of 16 bytes].  When
-        // accumulating, the old values are fetched two passes ahead so that their HBM latency
-        // overlaps the LDS turn-around and the stores.  Old values and results bypass L2
+        // accumulating, the old values are fetched kAhead passes ahead (two where the registers
+        // allow it) so that their HBM latency overlaps the LDS turn-around and the stores.  Old values and results bypass L2
         // retention (non-temporal) for the same reason as above.
         float* Cw = static_cast<float*>(C) + int64_t(row0) * N + col0 + cb * 4;
         auto gaddr = [&](int p, int it) { return Cw + int64_t((p >> 1) * 32 + it * 4 + rsub) * N + (p & 1) * 64; };
-        F4 old[3][8];
+        constexpr int kRing = kAhead + 1;
+        F4 old[kRing][8];
         auto fetch_old = [&](int p) {
 #pragma unroll
-            for (int it = 0; it < 8; ++it) old[p % 3][it] = __builtin_nontemporal_load(reinterpret_cast<const F4*>(gaddr(p, it)));
+            for (int it = 0; it < 8; ++it) old[p % kRing][it] = __builtin_nontemporal_load(reinterpret_cast<const F4*>(gaddr(p, it)));
         };
-        if (kAccumulate) { fetch_old(0); fetch_old(1); }
+        if (kAccumulate) {
+#pragma unroll
+            for (int p = 0; p < kAhead; ++p) fetch_old(p);
+        }
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
-            if (kAccumulate && p + 2 < 8) fetch_old(p + 2);
-            const int i = p >> 1, jh = p & 1;
+            if (kAccumulate && p + kAhead < 8) fetch_old(p + kAhead);
+            const int ps = p >> 1, jh = p & 1;
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int jj = 0; jj < 2; ++jj)
+            for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int c = 8 * jj + 2 * g + lhalf;
-                    const f32x16& a = acc[i][2 * jh + jj];
-                    *reinterpret_cast<F4*>(wlds + lrow * 256 + ((c ^ (lrow & 15)) << 4)) =
-                        F4{a[4 * g + 0], a[4 * g + 1], a[4 * g + 2], a[4 * g + 3]};
+                for (int jj = 0; jj < 4; ++jj) {
+                    const int c = 4 * jj + lq, r = 16 * h + lrow;
+                    const f32x4& a = acc[2 * ps + h][4 * jh + jj];
+                    *reinterpret_cast<F4*>(wlds + r * 256 + ((c ^ (r & 15)) << 4)) = F4{a[0], a[1], a[2], a[3]};
                 }
 #pragma unroll
             for (int it = 0; it < 8; ++it) {
                 const int m = it * 4 + rsub;
                 F4 v = *reinterpret_cast<const F4*>(wlds + m * 256 + ((cb ^ (m & 15)) << 4));
-                if (kAccumulate) v += old[p % 3][it];
+                if (kAccumulate) v += old[p % kRing][it];
                 __builtin_nontemporal_store(v, reinterpret_cast<F4*>(gaddr(p, it)));
             }
         }
@@ -454,7 +469,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     // deep operand has 1 3/4 steps to arrive and the shallow one a whole step.
     // Both are issued from one position (cur, kt): the deep loads read it directly, then a copy
     // of its shallow side is kept (`lag`) and the position moves on, in the middle of the step,
-    // without a branch (advance_0 .. advance_6 below).
+    // without a branch (the advance pieces below).
     StreamPos pos;
     pos.pi = 0;
     Run cur = stream_first<kTN>(pos, batch, int(blockIdx.x));
@@ -467,41 +482,66 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     auto deep = [](Run& r) -> Side& { return r.b; };
     auto shallow = [](Run& r) -> Side& { return r.a; };
 
-    // (cur, kt) -> next step of the stream; in parts so that each fits beside one MFMA.
+    // (cur, kt) -> next step of the stream; in pieces so that each fits beside one MFMA.
     // pick() takes values: a conditional expression over two variables is a choice between
     // their addresses, which would keep them in memory.
     // (the copies are written out so that they stay where they are put: as plain assignments the
     // compiler moves them to the top of the step, into the one slot that has no room)
-    auto keep_lag = [&]() {
+    auto keep_lag_s = [&]() {
         const Side& sh = shallow(cur);
         asm volatile("s_mov_b64 %0, %1" : "=s"(lag.g) : "s"(sh.g));
         asm volatile("s_mov_b64 %0, %1" : "=s"(lag.g2) : "s"(sh.g2));
-#pragma unroll
-        for (int p = 0; p < 4; ++p) asm volatile("v_mov_b32 %0, %1" : "=v"(lag.v[p]) : "v"(sh.v[p]));
     };
-    auto advance_0 = [&]() {
-        ++kt;
-        sw = kt == cur.nk;
-        cur.a.g = pick(sw, nxt.a.g, cur.a.g + step_bytes<kTN>(cur.a.ks));
-    };
-    auto advance_1 = [&]() { cur.a.g2 = pick(sw, nxt.a.g2, cur.a.g2 + step_bytes<kTN>(cur.a.ks)); };
-    auto advance_2 = [&]() { cur.b.g = pick(sw, nxt.b.g, cur.b.g + step_bytes<kTN>(cur.b.ks)); };
-    auto advance_3 = [&]() { cur.b.g2 = pick(sw, nxt.b.g2, cur.b.g2 + step_bytes<kTN>(cur.b.ks)); };
-    auto advance_4 = [&]() {
+    auto keep_lag_v = [&](int h) {
+        const Side& sh = shallow(cur);
 #pragma unroll
-        for (int p = 0; p < 4; ++p) cur.a.v[p] = pick(sw, nxt.a.v[p], cur.a.v[p]);
+        for (int p = 2 * h; p < 2 * h + 2; ++p) asm volatile("v_mov_b32 %0, %1" : "=v"(lag.v[p]) : "v"(sh.v[p]));
+    };
+    // Pieces of at most three instructions.  `ahead` holds a pointer one step further on until the
+    // next piece decides between it and the new run's.
+    const char* ahead;
+    auto adv_count = [&]() { ++kt; sw = kt == cur.nk; };
+    auto adv_add = [&](const char* g, uint32_t ks) { ahead = g + step_bytes<kTN>(ks); };
+    auto adv_sel = [&](const char*& g, const char* n) { g = pick(sw, n, ahead); };
+    auto adv_v = [&](Side& c, const Side& n, int p0, int p1) {
+#pragma unroll
+        for (int p = p0; p < p1; ++p) c.v[p] = pick(sw, n.v[p], c.v[p]);
+    };
+    auto adv_ks = [&]() {
         if (kTN) {
             cur.a.ks = pick(sw, nxt.a.ks, cur.a.ks);
             cur.b.ks = pick(sw, nxt.b.ks, cur.b.ks);
         }
     };
-    auto advance_5 = [&]() {
-#pragma unroll
-        for (int p = 0; p < 4; ++p) cur.b.v[p] = pick(sw, nxt.b.v[p], cur.b.v[p]);
+    auto adv_nk = [&]() {
         cur.nk = pick(sw, nxt.nk, cur.nk);
         kt = pick(sw, 0, kt);
     };
-    auto advance = [&]() { advance_0(); advance_1(); advance_2(); advance_3(); advance_4(); advance_5(); };
+    // piece number n of the position's move (0 .. kAdvancePieces-1)
+    constexpr int kAdvancePieces = 15;
+    auto advance_piece = [&](int n) {
+        switch (n) {
+            case 0: adv_count(); break;
+            case 1: adv_add(cur.a.g, cur.a.ks); break;
+            case 2: adv_sel(cur.a.g, nxt.a.g); break;
+            case 3: adv_add(cur.a.g2, cur.a.ks); break;
+            case 4: adv_sel(cur.a.g2, nxt.a.g2); break;
+            case 5: adv_add(cur.b.g, cur.b.ks); break;
+            case 6: adv_sel(cur.b.g, nxt.b.g); break;
+            case 7: adv_add(cur.b.g2, cur.b.ks); break;
+            case 8: adv_sel(cur.b.g2, nxt.b.g2); break;
+            case 9: adv_v(cur.a, nxt.a, 0, 3); break;
+            case 10: adv_v(cur.a, nxt.a, 3, 4); adv_v(cur.b, nxt.b, 0, 2); break;
+            case 11: adv_v(cur.b, nxt.b, 2, 4); break;
+            case 12: adv_ks(); break;
+            case 13: adv_nk(); break;
+            default: break;
+        }
+    };
+    auto advance = [&]() {
+#pragma unroll
+        for (int n = 0; n < kAdvancePieces; ++n) advance_piece(n);
+    };
 
     // Steps 0 and 1 in full; the position ends on step 2.
     fill_side<0, 8>(deep(cur), lds_wave_base);
@@ -526,20 +566,27 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     auto stage_a = [&](uint32_t d, uint32_t sh) { return lds + sh; };
     auto stage_b = [&](uint32_t d, uint32_t sh) { return lds + d; };
 
-    f32x16 acc[4][4];
-    bf16x8 fa[2][4], fb[2][4];
+    // 8 x 8 accumulator tiles of 16 x 16.  A sub-step (32 of the contraction) is 64 MFMAs, row by
+    // row of tiles.  The A operands live in one set of registers: operand i of the next sub-step is
+    // read as soon as row i of this one has been issued.  The B operands are needed by every row
+    // and are double-buffered.
+    f32x4 acc[8][8];
+    bf16x8 fa[8], fb[2][8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) fa[0][i] = load_frag<kTN>(stage_a(d0, s0), fr.a[i], 0);
+    for (int i = 0; i < 7; ++i) fa[i] = load_frag<kTN>(stage_a(d0, s0), fr.a[i], 0);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) fb[0][j] = load_frag<kTN>(stage_b(d0, s0), fr.b[j], 0);
+    for (int j = 0; j < 8; ++j) fb[0][j] = load_frag<kTN>(stage_b(d0, s0), fr.b[j], 0);
 
     // Stage offsets of the next step (written out for the same reason as keep_lag).
-    auto rotate_deep = [&]() {
-        uint32_t t;
-        asm volatile("s_mov_b32 %0, %1" : "=s"(t) : "s"(d0));
-        asm volatile("s_mov_b32 %0, %1" : "=s"(d0) : "s"(d1));
-        asm volatile("s_mov_b32 %0, %1" : "=s"(d1) : "s"(d2));
-        asm volatile("s_mov_b32 %0, %1" : "=s"(d2) : "s"(t));
+    uint32_t rot;
+    auto rotate_deep = [&](int h) {
+        if (h == 0) {
+            asm volatile("s_mov_b32 %0, %1" : "=s"(rot) : "s"(d0));
+            asm volatile("s_mov_b32 %0, %1" : "=s"(d0) : "s"(d1));
+        } else {
+            asm volatile("s_mov_b32 %0, %1" : "=s"(d1) : "s"(d2));
+            asm volatile("s_mov_b32 %0, %1" : "=s"(d2) : "s"(rot));
+        }
     };
     auto rotate_shallow = [&]() {
         uint32_t t;
@@ -548,8 +595,10 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
         asm volatile("s_mov_b32 %0, %1" : "=s"(s1) : "s"(t));
     };
 
-    // One contraction step of 64.  `first_tag` says whether it opens a tile: then its first
-    // 16 MFMAs take a zero constant as their addend.
+    // One contraction step of 64 = two sub-steps u of 64 MFMAs (slot (u, i, jj): row i of tiles,
+    // jj-th MFMA of the row).  `first_tag` says whether it opens a tile: then its first sub-step
+    // takes a zero constant as addend.  With one wave per SIMD a wave issues one instruction every
+    // 4 cycles and an MFMA occupies the matrix pipe for 16: three other instructions fit behind it.
     auto contraction_step = [&](auto first_tag) {
         constexpr bool kFirst = decltype(first_tag)::value;
         const char* cur_a = stage_a(d0, s0);
@@ -558,66 +607,78 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
         const char* nxt_b = stage_b(d1, s1);
         const uint32_t deep_fill = lds_wave_base + d2;
         const uint32_t shallow_fill = lds_wave_base + s0;
-        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
         // Issue order below is pinned with scheduling fences.
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            if (s == 3) {
-                // every operand read of this step's stages has been issued: wait for them and for
-                // this wave's part of the next step (all loads but the eight issued in the first
-                // quarter), then meet the other waves.  After the barrier the next step's stages
-                // are complete and this step's may be overwritten.
-                __builtin_amdgcn_s_waitcnt(0x0f78);     // vmcnt(8), other counters untouched
-                __syncthreads();
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            const char* rd_a = s == 3 ? nxt_a : cur_a;     // quarter 3 reads quarter 0 of the next step
-            const char* rd_b = s == 3 ? nxt_b : cur_b;
-            const int rs = s == 3 ? 0 : s + 1;
+        for (int u = 0; u < 2; ++u) {
 #pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                // boustrophedon over the 4 x 4 tiles: consecutive MFMAs always share an operand
-                // (slightly less switching in the matrix cores, which the power limit pays back)
-                const int i = q >> 2, j = (i & 1) ? 3 - (q & 3) : (q & 3);
-                // D rows <- n (B operand rows), D columns <- m: a lane then owns 4 consecutive n
-                // of one output row m, i.e. 4 contiguous elements of row-major C.
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[s & 1][j], fa[s & 1][i],
-                                                                   (kFirst && s == 0) ? zero : acc[i][j], 0, 0, 0);
-                if (q < 8) {
-                    // operand order A0 B0 A1 B1 A2 B2 A3 B3
-                    if (q & 1) fb[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd_b, fr.b[q >> 1], rs);
-                    else       fa[(s + 1) & 1][q >> 1] = load_frag<kTN>(rd_a, fr.a[q >> 1], rs);
+            for (int i = 0; i < 8; ++i) {
+                if (u == 1 && i == 4) {
+                    // every operand read of this step's stages has been issued: wait for them and
+                    // for this wave's part of the next step (all loads but the eight issued at the
+                    // start of this step), then meet the other waves.  After the barrier the next
+                    // step's stages are complete and this step's may be overwritten.
+                    __builtin_amdgcn_s_waitcnt(0x0f78);     // vmcnt(8), other counters untouched
+                    __syncthreads();
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                // One load after every second MFMA: the texture-address unit, which the waves
-                // share, is then never asked for more than it can take while the matrix cores run.
-                if (s == 0 && (q & 1)) {                 // deep operand of the step after the next
-                    switch (q >> 1) {
+#pragma unroll
+                for (int jj = 0; jj < 8; ++jj) {
+                    // boustrophedon over the tiles: consecutive MFMAs always share an operand
+                    const int j = (i & 1) ? 7 - jj : jj;
+                    // D rows <- n (B operand rows), D columns <- m: a lane then owns 4 consecutive n
+                    // of one output row m, i.e. 4 contiguous elements of row-major C.
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[u][j], fa[i],
+                                                                       (kFirst && u == 0) ? zero : acc[i][j], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);          // the MFMA first, then what rides behind it
+                    // --- operand reads ---
+                    // A operand 7 of this very sub-step: its registers were busy until the last row
+                    // of the sub-step before
+                    if (i == 0 && jj == 0) fa[7] = load_frag<kTN>(cur_a, fr.a[7], u);
+                    if (u == 0) {
+                        // next sub-step, same stage
+                        if (i >= 1 && jj == 0) fa[i - 1] = load_frag<kTN>(cur_a, fr.a[i - 1], 1);
+                        if (jj == 4) fb[1][i] = load_frag<kTN>(cur_b, fr.b[i], 1);
+                    } else if (i >= 4) {
+                        // first sub-step of the next step, after the barrier
+                        if (i == 4 && !(jj & 1)) fa[jj >> 1] = load_frag<kTN>(nxt_a, fr.a[jj >> 1], 0);
+                        if (i >= 5 && jj == 0) fa[i - 1] = load_frag<kTN>(nxt_a, fr.a[i - 1], 0);
+                        if (jj == 1) fb[0][2 * (i - 4)] = load_frag<kTN>(nxt_b, fr.b[2 * (i - 4)], 0);
+                        if (jj == 5) fb[0][2 * (i - 4) + 1] = load_frag<kTN>(nxt_b, fr.b[2 * (i - 4) + 1], 0);
+                    }
+                    // --- stage fills: one load after every fourth MFMA, the rate at which the
+                    // texture-address unit, which the waves share, takes them ---
+                    if (u == 0 && i < 4 && (jj == 2 || jj == 6)) {       // deep operand of the step after the next
+                        switch (2 * i + (jj >> 2)) {
 #define TF_FILL_CASE(Q) case Q: fill_load<Q>(deep(cur).g, deep(cur).g2, deep(cur).v, deep_fill); break;
-                        TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
-                        TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
+                            TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
+                            TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
 #undef TF_FILL_CASE
+                        }
                     }
-                }
-                // its shallow operand follows in the last quarter; until then the position moves on
-                if (s == 0 && q == 14) keep_lag();
-                if (s == 1 && q == 8) advance_0();
-                if (s == 1 && q == 9) advance_1();
-                if (s == 1 && q == 10) advance_2();
-                if (s == 1 && q == 11) advance_3();
-                if (s == 1 && q == 12) advance_4();
-                if (s == 1 && q == 13) advance_5();
-                if (s == 2 && q == 12) rotate_deep();     // the step itself works on copies taken at its top
-                if (s == 2 && q == 13) rotate_shallow();
-                if (s == 3 && !(q & 1)) {                // (the even slots: the last one stays free for the loop's back edge)
-                    switch (q >> 1) {
+                    if (u == 1 && i >= 4 && (jj == 3 || jj == 7)) {      // its shallow operand, into the stage just freed
+                        switch (2 * (i - 4) + (jj >> 2)) {
 #define TF_FILL_CASE(Q) case Q: fill_load<Q>(lag.g, lag.g2, lag.v, shallow_fill); break;
-                        TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
-                        TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
+                            TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
+                            TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
 #undef TF_FILL_CASE
+                        }
                     }
+                    // --- in between, the position moves on: pieces in the slots that hold nothing else ---
+                    if (u == 0 && i == 4 && jj == 1) keep_lag_s();
+                    if (u == 0 && i == 4 && jj == 2) keep_lag_v(0);
+                    if (u == 0 && i == 4 && jj == 3) keep_lag_v(1);
+                    if (u == 0 && i >= 5 && jj != 0 && jj != 4) {
+                        // rows 5, 6, 7: jj = 1, 2, 3, 5, 6, 7 -> pieces 0 .. 17
+                        const int n = 6 * (i - 5) + (jj < 4 ? jj - 1 : jj - 2);
+                        if (n < kAdvancePieces) advance_piece(n);
+                    }
+                    if (u == 1 && i == 0 && jj == 2) rotate_deep(0);     // the step itself works on copies taken at its top
+                    if (u == 1 && i == 0 && jj == 3) rotate_deep(1);
+                    if (u == 1 && i == 0 && jj == 5) rotate_shallow();
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
@@ -644,7 +705,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
         // The deep stage that the last step consumed (d2 after the rotation) is the epilogue's:
         // every wave is past that step's barrier, and its next fill is issued by the next step.
         const GemmProblem& P = batch.p[ct.pi];
-        store_block<kOutBf16, kAccumulate>(acc, lds + d2 + wave * kEpiBytes, P.C, P.N, ct.m0 + wm * 128, ct.n0 + wn * 128);
+        store_block<kOutBf16, kAccumulate, kTN ? 2 : 1>(acc, lds + d2 + wave * kEpiBytes, P.C, P.N, ct.m0 + wm * 128, ct.n0 + wn * 128);
         cvb += stride;
         if (cvb >= total) break;
         __syncthreads();          // no wave may fill that stage while another still turns its block around in it
