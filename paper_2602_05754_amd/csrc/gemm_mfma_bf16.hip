@@ -7,7 +7,7 @@
 //
 // Persistent workgroups: one per compute unit, each walking every gridDim.x-th
 // 256 x 256 output tile of the launch.  Four waves in a 2 x 2 grid, 128 x 128 per
-// wave = 4 x 4 MFMA 32x32x16 tiles, 256 accumulators per lane.  The contraction
+// wave = 8 x 8 MFMA 16x16x32 tiles, 256 accumulators per lane.  The contraction
 // advances 64 at a time through LDS stages of 32 KB per operand - two for A, three
 // for B, all of the 160 KB - that are filled by direct global->LDS loads (no
 // register staging): A's loads are issued one contraction step before they are
@@ -15,10 +15,11 @@
 // workgroup: while the matrix cores finish a tile, the first two contraction steps
 // of the next tile are already in flight, so a tile switch costs the epilogue and
 // nothing else - no drain, no refill, no new workgroup.
-// A stage is consumed in four steps of 16; the operands of step s + 1 are read
-// from LDS while the MFMAs of step s issue, the stage barrier sits after the reads
-// of the last step, and the first operands of the next stage are read during the
-// last step, so neither LDS latency nor the barrier leaves the matrix cores idle.
+// A stage is consumed in two sub-steps of 32 (64 MFMAs each); the operands of the
+// next sub-step are read from LDS while the MFMAs of this one issue, the stage
+// barrier sits after the last reads of the stage, and the first operands of the
+// next stage are read behind it during the last quarter, so neither LDS latency nor
+// the barrier leaves the matrix cores idle.
 // The first step of a tile multiplies into a zero constant instead of clearing
 // 256 registers.  The epilogue turns 32-row blocks around in 8 KB of LDS per wave,
 // inside the B stage that the tile's last step has finished with and that is filled
@@ -31,7 +32,7 @@
 //   kNT stage: [256 rows][64 contraction] per operand, 16-byte chunks of a row
 //              XOR-swizzled; MFMA operands are plain 128-bit LDS reads.
 //   kTN stage: [64 contraction][256 rows] per operand (the layout in memory),
-//              64-byte blocks of a row XOR-swizzled; MFMA operands come from the
+//              32-byte units of a row XOR-swizzled; MFMA operands come from the
 //              LDS transpose read (4 contraction values of one row per lane).
 // A direct-to-LDS load writes lane i's 16 bytes at (wave-uniform base) + 16 i,
 // so a swizzle is applied by choosing which global address each lane fetches.
@@ -126,7 +127,7 @@ __device__ __forceinline__ TilePos locate_tile(const GemmBatch& batch, int lt, i
 //   kNT: that KB is tile rows R = 8 (4 p + w) + lane/8, physical chunk lane%8 of each row;
 //        logical chunk = physical ^ ((R ^ (R >> 3)) & 7).
 //   kTN: that KB is contraction rows T = 2 (4 p + w) + lane/32, 16-byte slot lane%32 of
-//        each; logical 64-byte block = physical block ^ (T & 3).
+//        each; logical 32-byte unit = physical unit ^ (4 ((T / 8) % 4) + T % 4).
 // ---------------------------------------------------------------------------------------------
 struct Side {
     // One operand of a run.  Loads p = 0..3 of a stage fill go through (g, v[p]), loads 4..7
@@ -147,17 +148,15 @@ __device__ __forceinline__ Side make_side(const uint16_t* base, int64_t ld, int 
     Side f;
     if (kTN) {
         const int T = 2 * w + (lane >> 5);                     // + 8 p
-        const int slot = lane & 31;                            // 16-byte unit of the 512-byte row
-        // logical 32-byte unit = physical unit ^ f(T), f(T) = 4 ((T / 8) % 4) + T % 4: adding 8 p to T
-        // changes (T / 8) % 4 by p % 4, which is folded in below
-        const int col = 0;                                     // (worked out per p)
+        const int slot = lane & 31;                            // 16-byte slot of the 512-byte row
+        // logical 32-byte unit = physical unit ^ f(T), f(T) = 4 ((T / 8) % 4) + T % 4
         f.g = reinterpret_cast<const char*>(base + origin);
         f.g2 = f.g + 8 * kWaves * ld * 2;
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int Tp = T + 2 * kWaves * p;                 // loads p and p + 4 differ by 32 rows: the same f
             const int unit = (slot >> 1) ^ (4 * ((Tp >> 3) & 3) + (Tp & 3));
-            f.v[p] = uint32_t((int64_t(Tp) * ld + unit * 16 + (slot & 1) * 8 + col) * 2);
+            f.v[p] = uint32_t((int64_t(Tp) * ld + unit * 16 + (slot & 1) * 8) * 2);
         }
         f.ks = uint32_t(kBK * ld * 2);
     } else {
@@ -657,7 +656,8 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
 #undef TF_FILL_CASE
                         }
                     }
-                    if (u == 1 && i >= 4 && (jj == 3 || jj == 7)) {      // its shallow operand, into the stage just freed
+                    // (the very last slot stays free for the loop's back edge)
+                    if (u == 1 && i >= 4 && (jj == 3 || jj == (i == 7 ? 6 : 7))) {   // its shallow operand, into the stage just freed
                         switch (2 * (i - 4) + (jj >> 2)) {
 #define TF_FILL_CASE(Q) case Q: fill_load<Q>(lag.g, lag.g2, lag.v, shallow_fill); break;
                             TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
