@@ -97,6 +97,9 @@ class Stage:
         self.dX = [torch.empty((self.T, k), dtype=bf, device="cuda") for k, n in self.shapes]
         self.dW = [torch.zeros((k, n), dtype=bf, device="cuda") for k, n in self.shapes]
         self.sums = torch.zeros(2 * self.L, dtype=torch.float64, device="cuda")
+        # the same buffers go to the library step after step: marshal their pointers once
+        for name in ("p", "W", "X", "dY", "m", "v", "E", "A", "dX", "dW"):
+            setattr(self, name, tf.PtrTable(getattr(self, name)))
         self.steps = [1] * self.L
         self.hp = {k: float(np.float32(getattr(cfg, k))) for k in ("lr", "beta1", "beta2", "eps", "weight_decay")}
         self.decay = float(np.float32(cfg.ema_decay))

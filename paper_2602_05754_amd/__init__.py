@@ -4,7 +4,7 @@ App. D.1, Sec. 2.3).  Thin ctypes binding over the C-ABI library libtf.so;
 every step of the path runs in hand-written gfx950 kernels.  There is no CPU
 or PyTorch fallback: without the built library, calls raise."""
 from .binding import (  # noqa: F401
-    TF_BF16, TF_F32, Context, TfError, library_path, load_library,
+    TF_BF16, TF_F32, Context, PtrTable, TfError, library_path, load_library,
     tf_masked_adamw, tf_num_frozen, tf_select_lowest, tf_stability_scores,
     tf_stability_update, tf_stage_backward, tf_strerror, tf_version, EXPORTED_SYMBOLS, KERNEL_KINDS,
     tf_autofreeze_norms, tf_autofreeze_scores, tf_autofreeze_select, tf_reconcile_mask,

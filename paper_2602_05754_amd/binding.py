@@ -137,12 +137,41 @@ def _dptr(x) -> Optional[int]:
     return int(x.data_ptr())
 
 
+class PtrTable:
+    """A list of device buffers marshalled once: the host array of their pointers and their
+    sizes in bytes.  Pass it wherever a wrapper takes a list of tensors when the same list is
+    handed over call after call (a training loop): the wrapper then checks the sizes with one
+    vector comparison and builds nothing.  It holds references to the tensors."""
+
+    def __init__(self, seq):
+        self._items = list(seq)
+        n = len(self._items)
+        self.arr = (ctypes.c_void_p * max(n, 1))()
+        self.nbytes = np.full(n, np.iinfo(np.int64).max, dtype=np.int64)     # raw ints: size unknown
+        for i, x in enumerate(self._items):
+            self.arr[i] = _dptr(x)
+            if x is not None and not isinstance(x, int):
+                if not x.is_contiguous():
+                    raise ValueError(f"entry {i}: tensor must be contiguous")
+                self.nbytes[i] = x.numel() * x.element_size()
+        self.present = np.array([x is not None for x in self._items], dtype=bool)
+        self.ptr = ctypes.cast(self.arr, ctypes.c_void_p)
+
+    def __len__(self):
+        return len(self._items)
+
+    def __getitem__(self, i):
+        return self._items[i]
+
+
 def _ptr_array(seq, n):
     """Host array of n device pointers (NULL for None); None stays None."""
     if seq is None:
         return None, None
     if len(seq) != n:
         raise ValueError(f"expected {n} entries, got {len(seq)}")
+    if isinstance(seq, PtrTable):
+        return seq.arr, seq.ptr
     arr = (ctypes.c_void_p * max(n, 1))()
     for i, x in enumerate(seq):
         arr[i] = _dptr(x)
@@ -179,6 +208,26 @@ def _check_numel(x, numel, dtype_code, what):
                          f"{numel} elements of {_ELEM_SIZE[dtype_code]} bytes")
     if not x.is_contiguous():
         raise ValueError(f"{what}: tensor must be contiguous")
+
+
+def _check_seq(seq, numels, dtype_code, what, skip=None):
+    """_check_numel over a list of buffers; entries with skip[i] set are not looked at."""
+    if seq is None:
+        return
+    if isinstance(seq, PtrTable):
+        need = np.asarray(numels, dtype=np.int64) * _ELEM_SIZE[dtype_code]
+        bad = seq.present & (seq.nbytes < need)
+        if skip is not None:
+            bad &= ~np.asarray(skip, dtype=bool)
+        if bad.any():
+            i = int(np.flatnonzero(bad)[0])
+            raise ValueError(f"{what}[{i}]: buffer of {int(seq.nbytes[i])} bytes is smaller than "
+                             f"{int(numels[i])} elements of {_ELEM_SIZE[dtype_code]} bytes")
+        return
+    for i, x in enumerate(seq):
+        if skip is not None and skip[i]:
+            continue
+        _check_numel(x, int(numels[i]), dtype_code, f"{what}[{i}]")
 
 
 class Context:
@@ -258,15 +307,11 @@ def tf_stage_backward(ctx, shapes: Sequence[tuple], T: int, io_dtype: int,
     L = len(shapes)
     sh = np.ascontiguousarray(np.asarray(shapes, dtype=np.int64).reshape(L, 2))
     fm, fm_p = _host(freeze_mask, np.uint8, L)
-    for l in range(L):
-        K, N = int(sh[l, 0]), int(sh[l, 1])
-        frozen = fm is not None and fm[l]
-        if W is not None: _check_numel(W[l], K * N, io_dtype, f"W[{l}]")
-        if dY is not None: _check_numel(dY[l], T * N, io_dtype, f"dY[{l}]")
-        if dX is not None: _check_numel(dX[l], T * K, io_dtype, f"dX[{l}]")
-        if not frozen:
-            if X is not None: _check_numel(X[l], T * K, io_dtype, f"X[{l}]")
-            if dW is not None: _check_numel(dW[l], K * N, dw_dtype, f"dW[{l}]")
+    _check_seq(W, sh[:, 0] * sh[:, 1], io_dtype, "W")
+    _check_seq(dY, T * sh[:, 1], io_dtype, "dY")
+    _check_seq(dX, T * sh[:, 0], io_dtype, "dX")
+    _check_seq(X, T * sh[:, 0], io_dtype, "X", fm)
+    _check_seq(dW, sh[:, 0] * sh[:, 1], dw_dtype, "dW", fm)
     kW, pW = _ptr_array(W, L)
     kX, pX = _ptr_array(X, L)
     kdY, pdY = _ptr_array(dY, L)
@@ -290,15 +335,14 @@ def tf_masked_adamw(ctx, numel: Sequence[int], p_master, m, v, grad, grad_dtype:
     ne, ne_p = _host(numel, np.int64, n)
     st, st_p = _host(step, np.int32, n)
     fm, fm_p = _host(tensor_freeze_mask, np.uint8, n)
-    for i in range(n):
+    for name, seq, dt in (("p", p_master, TF_F32), ("m", m, TF_F32), ("v", v, TF_F32),
+                          ("grad", grad, grad_dtype), ("p_lowp", p_lowp, TF_BF16),
+                          ("ema", ema, TF_F32), ("ema_abs", ema_abs, TF_F32)):
+        _check_seq(seq, ne, dt, name, fm)
+    for i in range(n if elem_freeze_bits is not None else 0):
         if fm is not None and fm[i]:
             continue
-        for name, seq, dt in (("p", p_master, TF_F32), ("m", m, TF_F32), ("v", v, TF_F32),
-                              ("grad", grad, grad_dtype), ("p_lowp", p_lowp, TF_BF16),
-                              ("ema", ema, TF_F32), ("ema_abs", ema_abs, TF_F32)):
-            if seq is not None:
-                _check_numel(seq[i], int(ne[i]), dt, f"{name}[{i}]")
-        if elem_freeze_bits is not None and elem_freeze_bits[i] is not None and not isinstance(elem_freeze_bits[i], int):
+        if elem_freeze_bits[i] is not None and not isinstance(elem_freeze_bits[i], int):
             if elem_freeze_bits[i].numel() * elem_freeze_bits[i].element_size() < 4 * ((int(ne[i]) + 31) // 32):
                 raise ValueError(f"elem_freeze_bits[{i}] too small")
     if score_sums is not None and not isinstance(score_sums, int):

@@ -235,3 +235,31 @@ def test_row_block_entry_points_validate_before_any_gpu_work():
     assert _code(tf.tf_row_blocks_to_bits, None, [(8, 8)], [[0, 1]], 4, [A]) == INV
     assert _code(tf.tf_row_blocks_to_bits, None, [(8, 6)], [[0, 1]], 4, [A]) == SHAPE     # 4 x 6 elements: not whole words
     assert _code(tf.tf_row_blocks_to_bits, None, [(8, 8)], [[0, 1]], 4, [A + 1]) == ALIGN
+
+
+def test_pointer_tables_marshal_once_and_check_sizes():
+    """A PtrTable stands in for a list of buffers: same pointers, same validation outcome, and the
+    size check still catches a buffer that is too small (host tensors here: nothing is launched)."""
+    import torch
+    K, N, T = 8, 8, 4
+    mk = lambda n, dt=torch.float32: torch.zeros(n, dtype=dt)
+    W, X, dY, dX, dW = [mk(K * N)], [mk(T * K)], [mk(T * N)], [mk(T * K)], [mk(K * N)]
+    tabs = [tf.PtrTable(x) for x in (W, X, dY, dX, dW)]
+    assert all(t.arr[0] == x[0].data_ptr() and len(t) == 1 and t[0] is x[0] for t, x in zip(tabs, (W, X, dY, dX, dW)))
+    call = lambda w, x, dy, dx, dw, fm=(0,): _code(tf.tf_stage_backward, None, [(K, N)], T, tf.TF_F32, w, x, dy,
+                                                   list(fm), dx, dw, tf.TF_F32)
+    assert call(*tabs) == call(W, X, dY, dX, dW) == -1          # only the NULL ctx is left to complain about
+    small = tf.PtrTable([mk(K * N - 1)])
+    with pytest.raises(ValueError):
+        call(small, *tabs[1:])
+    with pytest.raises(ValueError):
+        call(tabs[0], tabs[1], tabs[2], tabs[3], small)
+    assert call(tabs[0], tabs[1], tabs[2], tabs[3], small, fm=(1,)) == -1   # frozen: dW is not looked at
+    with pytest.raises(ValueError):
+        tf.PtrTable([torch.zeros(4, 4).t()])                    # not contiguous
+    # raw integers carry no size: they pass the size check and reach the library's own validation
+    assert _code(tf.tf_masked_adamw, None, [64], tf.PtrTable([8192]), [8192], [8192], [8192], tf.TF_BF16, [1],
+                 1e-4, 0.9, 0.95, 1e-8, 0.1) == -1
+    with pytest.raises(ValueError):
+        tf.tf_masked_adamw(None, [64], tf.PtrTable([mk(63)]), [8192], [8192], [8192], tf.TF_BF16, [1],
+                           1e-4, 0.9, 0.95, 1e-8, 0.1)
