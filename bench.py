@@ -97,6 +97,7 @@ class Stage:
         self.dX = [torch.empty((self.T, k), dtype=bf, device="cuda") for k, n in self.shapes]
         self.dW = [torch.zeros((k, n), dtype=bf, device="cuda") for k, n in self.shapes]
         self.sums = torch.zeros(2 * self.L, dtype=torch.float64, device="cuda")
+        self.sums_host = torch.zeros(2 * self.L, dtype=torch.float64, pin_memory=True)
         # the same buffers go to the library step after step: marshal their pointers once
         for name in ("p", "W", "X", "dY", "m", "v", "E", "A", "dX", "dW"):
             setattr(self, name, tf.PtrTable(getattr(self, name)))
@@ -122,8 +123,9 @@ class Stage:
         tf.tf_stage_backward(ctx, self.shapes, self.T, tf.TF_BF16, self.W, self.X, self.dY, mask,
                              self.dX, self.dW, tf.TF_BF16)
         self.adamw(ctx, self.dW, mask)
-        sums_host = self.sums.cpu().numpy()                      # synchronises the stream
-        scores = tf.tf_stability_scores(sums_host)
+        self.sums_host.copy_(self.sums, non_blocking=True)       # into pinned memory: no staging copy
+        self.torch.cuda.current_stream().synchronize()           # the step ends here: the scores pick the next mask
+        scores = tf.tf_stability_scores(self.sums_host.numpy())
         return tf.tf_select_lowest(scores, n_freeze)
 
 
