@@ -59,7 +59,6 @@ static_assert(kWaves * kEpiBytes == kTileBytes, "the four epilogue areas fill on
 constexpr int kGroupM = 8;                            // tile rows per L2 locality group
 constexpr int kXcds = 8;
 constexpr int kXcdRun = 32;                           // consecutive logical tiles kept on one XCD
-constexpr int kLoads = 16;                            // 1 KB loads per wave and stage fill (8 per operand)
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -562,8 +561,8 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     // the next one, d2 is the deep stage that this step's first quarter fills.
     uint32_t d0 = 0, d1 = kTileBytes, d2 = 2 * kTileBytes;
     uint32_t s0 = kShallowBase, s1 = kShallowBase + kTileBytes;
-    auto stage_a = [&](uint32_t d, uint32_t sh) { return lds + sh; };
-    auto stage_b = [&](uint32_t d, uint32_t sh) { return lds + d; };
+    auto stage_a = [&](uint32_t, uint32_t sh) { return lds + sh; };     // A is the shallow operand
+    auto stage_b = [&](uint32_t d, uint32_t) { return lds + d; };       // B the deep one
 
     // 8 x 8 accumulator tiles of 16 x 16.  A sub-step (32 of the contraction) is 64 MFMAs, row by
     // row of tiles.  The A operands live in one set of registers: operand i of the next sub-step is
