@@ -172,3 +172,17 @@ def test_persistent_workgroups_crossing_many_short_tiles(ctx):
                                 np.ones(4, np.uint8), None, 0, [0, -1, 0, -1], out, None, tf.TF_BF16)
     torch.cuda.synchronize()
     assert rel_fro(host64(shared), ref_dX[0] + ref_dX[2]) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("shapes,T", [
+    ([(256, 64)], 256),              # dX on the matrix cores: ONE tile of ONE contraction step, one workgroup
+    ([(256, 256)], 64),              # dW on the matrix cores: one tile of one step (dX, 64 rows, on the generic kernel)
+    ([(512, 128), (256, 64)], 256),  # dX: two tiles of two steps, then one of one step
+    ([(256, 256), (256, 256)], 128), # dW: two problems of one tile and two steps each
+])
+def test_launches_smaller_than_the_fill_streams_lead(ctx, shapes, T):
+    """The fill stream of a workgroup runs two contraction steps ahead of the matrix cores.  With
+    fewer steps than that in the whole launch it reaches the end of its work before the first step
+    is consumed and has to stand still on the last step without reading past any buffer."""
+    L = len(shapes)
+    _case(ctx, shapes, T, "bf16", 256, np.zeros(L, np.uint8), None, seed=5)
