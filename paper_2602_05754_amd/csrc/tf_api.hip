@@ -121,6 +121,7 @@ hipError_t launch_planned(tf_ctx* ctx, hipStream_t stream, std::vector<Planned>&
                 if (slots > kMaxProblemsPerLaunch) return hipErrorInvalidValue;
                 if (n + slots > kMaxProblemsPerLaunch) break;
                 const int64_t nt = ((it.M + tile - 1) / tile) * ((it.N + tile - 1) / tile);
+                if (nt > 0x3fffffff) return hipErrorInvalidValue;      // tile indices are 32-bit on the device
                 if (n > 0 && tiles + nt > 0x3fffffff) break;
                 fill(batch.p[n], it, tiles, slots);
                 tiles += nt;
