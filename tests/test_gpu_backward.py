@@ -148,3 +148,21 @@ def test_degenerate_calls(ctx):
     with pytest.raises(ValueError):     # binding refuses a buffer smaller than the shape says
         tf.tf_stage_backward(ctx, [(512, 512)], 256, tf.TF_BF16, [gdX[0]], [gdX[0]], [gdX[0]], None,
                              [gdX[0]], [gdX[0]], tf.TF_BF16)
+
+
+def test_pointer_tables_give_the_same_bytes_as_lists(ctx):
+    """The binding's pre-marshalled pointer tables are marshalling only: the same call through
+    them writes the same bytes."""
+    cfg = wl.scaled(wl.CONFIGS[2], blocks=1, d=512, kv=256, ffn=768, T=512)
+    sh, T = cfg.shapes, cfg.T
+    W, X, dY = _inputs(cfg, T)
+    mask = wl.permutation_mask(cfg, 0.5)
+    gW, gX, gdY = ([dev(a, cfg.dtype) for a in t] for t in (W, X, dY))
+    out = []
+    for wrap in (list, tf.PtrTable):
+        gdX = [canary((T, k), torch.bfloat16) for k, n in sh]
+        gdW = [canary((k, n), torch.bfloat16) for k, n in sh]
+        tf.tf_stage_backward(ctx, sh, T, tf.TF_BF16, wrap(gW), wrap(gX), wrap(gdY), mask, wrap(gdX), wrap(gdW), tf.TF_BF16)
+        torch.cuda.synchronize()
+        out.append([raw_bytes(t) for t in gdX + gdW])
+    assert out[0] == out[1]
