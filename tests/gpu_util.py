@@ -32,6 +32,26 @@ def rel_fro(got: np.ndarray, ref: np.ndarray) -> float:
     return float(num / den) if den > 0 else float(num)
 
 
+def assert_elementwise(got, exact, dtype: str, label: str, scale: float = 1.0) -> None:
+    """Every element within the bound that one rounding of an fp32-accumulated sum allows:
+    bf16 storage |got - exact| <= 2^-8 |exact| + 1e-3 rms(exact), fp32 storage
+    |got - exact| <= 1e-5 (|exact| + rms(exact)); `scale` widens the fp32 bound for sums of
+    bf16 products accumulated over several calls."""
+    exact = np.asarray(exact, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    assert got.shape == exact.shape, f"{label}: shape {got.shape} against {exact.shape}"
+    rms = float(np.sqrt(np.mean(exact ** 2))) if exact.size else 0.0
+    if dtype == "bf16":
+        bound = 2.0 ** -8 * np.abs(exact) + 1e-3 * rms
+    else:
+        bound = scale * 1e-5 * (np.abs(exact) + rms)
+    bad = ~(np.abs(got - exact) <= bound)          # a NaN in `got` fails
+    if bad.any():
+        i = np.unravel_index(int(np.argmax(np.where(bad, np.abs(got - exact), 0.0))), exact.shape)
+        raise AssertionError(f"{label}: {int(bad.sum())} of {bad.size} elements off, worst at {i}: "
+                             f"got {got[i]:.6e} exact {exact[i]:.6e} (rms {rms:.3e})")
+
+
 def canary(shape, torch_dtype) -> torch.Tensor:
     """Device buffer filled with a recognisable non-trivial bit pattern (NaN payloads)."""
     n = int(np.prod(shape))

@@ -203,3 +203,76 @@ def test_warmup_then_lowest_score_selection_matches_the_oracle(ctx):
         gap = srt[n] - srt[n - 1] if 0 < n < L else np.inf
         assert gap > 100 * err, "selection boundary too tight for this seed"
         assert np.array_equal(tf.tf_select_lowest(got, n), ref_mask)
+
+
+def test_more_tensors_than_one_launch_holds(ctx):
+    """80 tensors, 11 of them frozen: the unfrozen 69 take three launches of at most 32
+    descriptors, each of which clears and accumulates its own tensors' sums; two steps in a
+    row on the same state (App. D.1; Sec. 2.3)."""
+    rs = np.random.default_rng(15)
+    n_t = 80
+    sizes = [int(x) for x in rs.integers(1, 9000, n_t)]
+    sizes[5], sizes[40], sizes[70] = 16384 * 2 + 3, 4096 * 4, 1            # several blocks, exact blocks, one element
+    states = [State(rs, n, zero_state=(i % 3 == 0), grad_dtype="bf16") for i, n in enumerate(sizes)]
+    tensor_mask = np.zeros(n_t, np.uint8)
+    tensor_mask[[0, 7, 31, 32, 33, 50, 63, 64, 65, 78, 79]] = 1
+    elem = [(rs.random(n) < 0.5).astype(np.uint8) if i % 4 == 1 else None for i, n in enumerate(sizes)]
+    bits = [None if e is None else torch.from_numpy(wl.pack_mask_bits(e).view(np.int32)).cuda() for e in elem]
+    sums = torch.full((2 * n_t,), -7.0, dtype=torch.float64, device="cuda")
+    steps = [int(x) for x in rs.integers(1, 6, n_t)]
+    for rep in range(2):
+        grads = [s.grad(rs) for s in states]
+        before = [{k: raw_bytes(s.d[k]) for k in s.d} for s in states]
+        for i, s in enumerate(states):
+            if not tensor_mask[i]:
+                oracle.masked_adamw(s.h["p"], s.h["m"], s.h["v"], grads[i].astype(np.float64), step=steps[i] + rep,
+                                    p_lowp=s.h["low"], elem_frozen=elem[i], ema=s.h["E"], ema_abs=s.h["A"],
+                                    ema_decay=DECAY, **HP)
+        tf.tf_masked_adamw(ctx, sizes, [s.d["p"] for s in states], [s.d["m"] for s in states],
+                           [s.d["v"] for s in states], [dev(g, "bf16") for g in grads], tf.TF_BF16,
+                           [t + rep for t in steps], HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"],
+                           p_lowp=[s.d["low"] for s in states], tensor_freeze_mask=tensor_mask, elem_freeze_bits=bits,
+                           ema=[s.d["E"] for s in states], ema_abs=[s.d["A"] for s in states], ema_decay=DECAY,
+                           score_sums=sums)
+        torch.cuda.synchronize()
+        _check(states, elem, tensor_mask, before, label=f"step {rep}")
+        got = sums.cpu().numpy().reshape(-1, 2)
+        for i, s in enumerate(states):
+            if tensor_mask[i]:
+                assert got[i].tolist() == [-7.0, -7.0], i
+            else:
+                se, sa = oracle.score_sums(s.h["E"], s.h["A"])
+                assert np.isclose(got[i, 0], se, rtol=1e-5, atol=1e-30) and np.isclose(got[i, 1], sa, rtol=1e-5, atol=1e-30), i
+
+
+def test_standalone_stability_update_with_more_tensors_than_one_launch_holds(ctx):
+    rs = np.random.default_rng(16)
+    n_t = 75
+    sizes = [int(x) for x in rs.integers(1, 6000, n_t)]
+    sizes[10] = 16384 + 5
+    f32 = lambda a: np.ascontiguousarray(a, np.float32)
+    E0 = [f32(rs.standard_normal(n) * 1e-5) for n in sizes]
+    A0 = [f32(np.abs(rs.standard_normal(n)) * 1e-4) for n in sizes]
+    D = [f32(rs.standard_normal(n) * 1e-4) for n in sizes]
+    tmask = np.zeros(n_t, np.uint8); tmask[[3, 31, 32, 64, 74]] = 1
+    elem = [(rs.random(n) < 0.3).astype(np.uint8) if i % 5 == 2 else None for i, n in enumerate(sizes)]
+    bits = [None if e is None else torch.from_numpy(wl.pack_mask_bits(e).view(np.int32)).cuda() for e in elem]
+    Eh = [a.astype(np.float64) for a in E0]; Ah = [a.astype(np.float64) for a in A0]
+    Ed = [dev(a, "f32") for a in E0]; Ad = [dev(a, "f32") for a in A0]
+    sums = torch.full((2 * n_t,), -3.0, dtype=torch.float64, device="cuda")
+    tf.tf_stability_update(ctx, sizes, [dev(d, "f32") for d in D], Ed, Ad, DECAY, tensor_freeze_mask=tmask,
+                           elem_freeze_bits=bits, score_sums=sums)
+    torch.cuda.synchronize()
+    got = sums.cpu().numpy().reshape(n_t, 2)
+    for i in range(n_t):
+        if tmask[i]:
+            assert raw_bytes(Ed[i]) == E0[i].tobytes() and raw_bytes(Ad[i]) == A0[i].tobytes(), i
+            assert got[i].tolist() == [-3.0, -3.0], i
+            continue
+        oracle.stability_update(D[i].astype(np.float64), Eh[i], Ah[i], DECAY, elem_frozen=elem[i])
+        assert rel_fro(host64(Ed[i]), Eh[i]) <= 1e-5 and rel_fro(host64(Ad[i]), Ah[i]) <= 1e-5, i
+        if elem[i] is not None:
+            f = elem[i].astype(bool)
+            assert np.array_equal(Ed[i].cpu().numpy()[f], E0[i][f]) and np.array_equal(Ad[i].cpu().numpy()[f], A0[i][f]), i
+        se, sa = oracle.score_sums(Eh[i], Ah[i])
+        assert np.isclose(got[i, 0], se, rtol=1e-5, atol=1e-30) and np.isclose(got[i, 1], sa, rtol=1e-5, atol=1e-30), i

@@ -8,7 +8,7 @@ import torch
 import oracle
 import workloads as wl
 import paper_2602_05754_amd as tf
-from gpu_util import CODE, TDT, TOL, canary, dev, host64, raw_bytes, rel_fro
+from gpu_util import CODE, TDT, TOL, assert_elementwise, canary, dev, host64, raw_bytes, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -56,11 +56,13 @@ def _run_case(ctx, cfg, T, mask, tol):
     for l in range(len(sh)):
         e = rel_fro(host64(gdX[l]), dXo[l]); worst = max(worst, e)
         assert e <= tol, f"dX[{l}] {sh[l]} rel_fro {e:.3e}"
+        assert_elementwise(host64(gdX[l]), dXo[l], cfg.dtype, f"dX[{l}] {sh[l]}")
         if mask[l]:
             assert raw_bytes(gdW[l]) == before[l], f"frozen dW[{l}] was touched"
         else:
             e = rel_fro(host64(gdW[l]), dWo[l]); worst = max(worst, e)
             assert e <= tol, f"dW[{l}] {sh[l]} rel_fro {e:.3e}"
+            assert_elementwise(host64(gdW[l]), dWo[l], cfg.dw_dtype, f"dW[{l}] {sh[l]}")
     return [raw_bytes(t) for t in gdX], worst
 
 
@@ -121,12 +123,14 @@ def test_fp32_accumulation_over_microbatches_with_per_microbatch_masks(ctx, dims
         torch.cuda.synchronize()
         for l in range(L):
             assert rel_fro(host64(gdX[l]), dXo[l]) <= TOL["bf16"]
+            assert_elementwise(host64(gdX[l]), dXo[l], "bf16", f"dX[{l}] microbatch {m}")
     for l in range(L):
         if always[l]:
             assert raw_bytes(gacc[l]) == before[l]
         else:
             e = rel_fro(host64(gacc[l]), acc_o[l])
             assert e <= 1e-5 * 10, f"acc[{l}] rel_fro {e:.3e}"   # fp32 accumulation of bf16 products
+            assert_elementwise(host64(gacc[l]), acc_o[l], "f32", f"acc[{l}]", scale=10.0)
 
 
 def test_degenerate_calls(ctx):
@@ -141,6 +145,7 @@ def test_degenerate_calls(ctx):
     dXo, _ = _oracle_backward(cfg, cfg.T, W, X, dY, np.ones(7, np.uint8))
     for l in range(7):
         assert rel_fro(host64(gdX[l]), dXo[l]) <= TOL["bf16"]
+        assert_elementwise(host64(gdX[l]), dXo[l], "bf16", f"dX[{l}]")
     # errors are reported, not raised as faults
     with pytest.raises(tf.TfError) as ei:
         tf.tf_stage_backward(ctx, cfg.shapes, 0, tf.TF_BF16, gdX, gdX, gdX, None, gdX, gdX, tf.TF_BF16)
@@ -166,3 +171,13 @@ def test_pointer_tables_give_the_same_bytes_as_lists(ctx):
         torch.cuda.synchronize()
         out.append([raw_bytes(t) for t in gdX + gdW])
     assert out[0] == out[1]
+
+
+def test_more_layers_than_one_grouped_launch_holds(ctx):
+    """77 small layers on the matrix cores: 64 problem descriptors per launch, so both halves of
+    the backward take a second launch (the weight-gradient half because 70 layers stay
+    unfrozen); several contraction lengths so that the cost order differs from the layer order."""
+    cfg = wl.scaled(wl.CONFIGS[2], blocks=11, d=256, kv=512, ffn=768, T=256)
+    mask = np.zeros(cfg.n_layers, np.uint8)
+    mask[[0, 9, 30, 31, 64, 65, 76]] = 1
+    _run_case(ctx, cfg, cfg.T, mask, TOL["bf16"])

@@ -10,7 +10,7 @@ import torch
 import oracle
 import workloads as wl
 import paper_2602_05754_amd as tf
-from gpu_util import CODE, TDT, TOL, canary, dev, host64, raw_bytes, rel_fro
+from gpu_util import CODE, TDT, TOL, assert_elementwise, canary, dev, host64, raw_bytes, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -49,6 +49,7 @@ def _case(ctx, shapes, T, dtype, block_rows, freeze_mask, row_masks, seed):
     it = 4 if dtype == "f32" else 2
     for l, (k, n) in enumerate(shapes):
         assert rel_fro(host64(gdX[l]), ref_dX[l]) <= TOL[dtype], f"dX[{l}]"
+        assert_elementwise(host64(gdX[l]), ref_dX[l], dtype, f"dX[{l}]")
         if freeze_mask is not None and freeze_mask[l]:
             assert raw_bytes(gdW[l]) == raw_bytes(before[l]), f"frozen dW[{l}] was touched"
             continue
@@ -60,6 +61,7 @@ def _case(ctx, shapes, T, dtype, block_rows, freeze_mask, row_masks, seed):
                 assert raw_bytes(got[rows]) == raw_bytes(before[l][rows]), f"frozen rows {rows} of dW[{l}] were touched"
             else:
                 assert rel_fro(host64(got[rows]), ref_dW[l][rows]) <= TOL[dtype], f"dW[{l}] rows {rows}"
+                assert_elementwise(host64(got[rows]), ref_dW[l][rows], dtype, f"dW[{l}] rows {rows}")
     return gW, gX, gdY, gdW
 
 
@@ -145,6 +147,7 @@ def test_fp32_accumulation_with_a_different_row_mask_per_microbatch(ctx):
     torch.cuda.synchronize()
     for l in range(2):
         assert rel_fro(host64(acc[l]), ref[l]) <= 1e-4, l
+        assert_elementwise(host64(acc[l]), ref[l], "f32", f"acc[{l}]", scale=10.0)
 
 
 def test_persistent_workgroups_crossing_many_short_tiles(ctx):
@@ -164,6 +167,7 @@ def test_persistent_workgroups_crossing_many_short_tiles(ctx):
     torch.cuda.synchronize()
     for l in range(4):
         assert rel_fro(host64(gdX[l]), ref_dX[l]) <= TOL["bf16"], l
+        assert_elementwise(host64(gdX[l]), ref_dX[l], "bf16", f"dX[{l}]")
     # the same with the first three layers as one input group is refused (different widths), with
     # layers 0 and 2 grouped (both 4096 wide) it is one problem of 1 + 3 steps
     shared = canary((T, 4096), torch.bfloat16)
@@ -172,6 +176,7 @@ def test_persistent_workgroups_crossing_many_short_tiles(ctx):
                                 np.ones(4, np.uint8), None, 0, [0, -1, 0, -1], out, None, tf.TF_BF16)
     torch.cuda.synchronize()
     assert rel_fro(host64(shared), ref_dX[0] + ref_dX[2]) <= TOL["bf16"]
+    assert_elementwise(host64(shared), ref_dX[0] + ref_dX[2], "bf16", "grouped dX of layers 0 and 2")
 
 
 @pytest.mark.parametrize("shapes,T", [

@@ -56,13 +56,19 @@ def _check(got, exact, label, tol_fro=1e-2):
     return e
 
 
-def _backward_case(ctx, cfg, r, seed):
-    sh, T, L = cfg.shapes, cfg.T, cfg.n_layers
+def _prepare(cfg):
+    """Host arrays (W, X, dY per layer) and their device copies."""
     host = _gen(cfg)
-    mask = wl.permutation_mask(cfg, r)
     gW = [dev(h[0], "bf16") for h in host]
     gX = [dev(h[1], "bf16") for h in host]
     gdY = [dev(h[2], "bf16") for h in host]
+    return host, gW, gX, gdY
+
+
+def _backward_case(ctx, cfg, r, seed, prepared=None):
+    sh, T, L = cfg.shapes, cfg.T, cfg.n_layers
+    host, gW, gX, gdY = prepared if prepared is not None else _prepare(cfg)
+    mask = wl.permutation_mask(cfg, r)
     gdX = [canary((T, k), torch.bfloat16) for k, n in sh]
     gdW = [canary((k, n), torch.bfloat16) for k, n in sh]
     before = [t.clone() for t in gdW]
@@ -106,10 +112,64 @@ def test_llama1b_stage_full_size_as_benchmarked(ctx):
     print(f"cfg2 worst sampled rel_fro {worst:.2e}")
 
 
-def test_llama8b_stage_shapes(ctx):
-    # BASELINE configs[2] layer shapes (d=4096, kv=1024, ffn=14336, 4096 tokens); 2 of the 8 blocks
-    worst = _backward_case(ctx, wl.scaled(wl.CONFIGS[3], blocks=2), 0.5, seed=22)
-    print(f"cfg3 (2 blocks) worst sampled rel_fro {worst:.2e}")
+def test_llama8b_stage_all_eight_blocks(ctx):
+    """BASELINE configs[2] in full: 8 blocks, 56 layers (d=4096, kv=1024, ffn=14336, 4096 tokens) - one
+    grouped launch of 19,456 input-gradient tiles and one of up to 26,624 weight-gradient tiles, 15 GB of
+    operands and outputs (tensors lie on both sides of several 4 GiB address boundaries) - at
+    r = 0, 0.5 and 0.9 (28 and 51 of 56 tensors frozen); at least two sampled elements per output tile."""
+    cfg = wl.CONFIGS[3]
+    prepared = _prepare(cfg)
+    for r, n_frozen in ((0.0, 0), (0.5, 28), (0.9, 51)):
+        assert int(wl.permutation_mask(cfg, r).sum()) == n_frozen
+        worst = _backward_case(ctx, cfg, r, seed=22 + int(10 * r), prepared=prepared)
+        print(f"cfg3 r={r} worst sampled rel_fro {worst:.2e}")
+
+
+def test_operands_and_outputs_that_cross_a_4gib_address_boundary(ctx):
+    """Every tensor of a layer in turn is laid across a multiple of 2^32 in the device address
+    space, so that the fill addresses of some tile (inputs) or the rows of some tile's epilogue
+    (outputs) carry into the high word; whole outputs against the oracle."""
+    from gpu_util import assert_elementwise
+    k, n, T = 1024, 512, 512
+    cfg = wl.scaled(wl.CONFIGS[2], blocks=1, d=k, kv=n, ffn=256, T=T)
+    W, X, dY = wl.gen_layer(cfg, 1)                       # layer 1 is the (d, kv) projection
+    assert W.shape == (k, n)
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    ref_dX = [np.zeros((T, k))]; ref_dW = [np.zeros((k, n))]
+    oracle.stage_backward([(k, n)], T, [f64(W)], [f64(X)], [f64(dY)], np.zeros(1, np.uint8), ref_dX, ref_dW)
+    span = (1 << 32) + (64 << 20)
+    pool = torch.empty(span, dtype=torch.uint8, device="cuda")
+    base = pool.data_ptr()
+    edge = (-base) % (1 << 32)                            # offset of the first multiple of 2^32 inside the pool
+    if edge < (2 << 20):                                  # too close to the start for a tensor to begin before it
+        edge += 1 << 32
+    assert edge + (32 << 20) <= span
+    sizes = {"W": k * n, "X": T * k, "dY": T * n, "dX": T * k, "dW": k * n}
+    shapes = {"W": (k, n), "X": (T, k), "dY": (T, n), "dX": (T, k), "dW": (k, n)}
+    src = {"W": W, "X": X, "dY": dY}
+    for across in ("W", "X", "dY", "dX", "dW"):
+        # the chosen tensor starts 16 (mod 32) bytes before the middle of its bytes reaches the edge,
+        # so the edge falls inside a row; the others are packed well away from it
+        off = {}
+        cursor = 0 if edge > (32 << 20) else edge + (16 << 20)
+        for name in sizes:
+            if name == across:
+                off[name] = edge - ((sizes[name] * 2 // 2 + 16) // 16) * 16
+            else:
+                off[name] = cursor
+                cursor += sizes[name] * 2 + 256
+        view = {name: pool[off[name]: off[name] + 2 * sizes[name]].view(torch.bfloat16).view(shapes[name]) for name in sizes}
+        lo, hi = base + off[across], base + off[across] + 2 * sizes[across]
+        assert lo >> 32 != (hi - 1) >> 32, "the tensor does not cross the boundary"
+        for name in src:
+            view[name].copy_(dev(src[name], "bf16"))
+        view["dX"].copy_(canary((T, k), torch.bfloat16)); view["dW"].copy_(canary((k, n), torch.bfloat16))
+        tf.tf_stage_backward(ctx, [(k, n)], T, tf.TF_BF16, [view["W"]], [view["X"]], [view["dY"]], np.zeros(1, np.uint8),
+                             [view["dX"]], [view["dW"]], tf.TF_BF16)
+        torch.cuda.synchronize()
+        assert_elementwise(host64(view["dX"]), ref_dX[0], "bf16", f"dX with {across} across the boundary")
+        assert_elementwise(host64(view["dW"]), ref_dW[0], "bf16", f"dW with {across} across the boundary")
+    del pool
 
 
 def test_llama8b_microbatch_accumulation_then_masked_update(ctx):

@@ -9,7 +9,7 @@ import torch
 import oracle
 import workloads as wl
 import paper_2602_05754_amd as tf
-from gpu_util import CODE, TDT, TOL, canary, dev, host64, raw_bytes, rel_fro
+from gpu_util import CODE, TDT, TOL, assert_elementwise, canary, dev, host64, raw_bytes, rel_fro
 
 pytestmark = pytest.mark.gpu
 
@@ -55,10 +55,12 @@ def _run(ctx, shapes, groups, T, dtype, freeze_mask, seed):
     torch.cuda.synchronize()
     for l in range(L):
         assert rel_fro(host64(gdX[l]), ref_dX[l]) <= TOL[dtype], f"dX[{l}]"
+        assert_elementwise(host64(gdX[l]), ref_dX[l], dtype, f"dX[{l}]")
         if fm[l]:
             assert raw_bytes(gdW[l]) == raw_bytes(before[l])
         else:
             assert rel_fro(host64(gdW[l]), ref_dW[l]) <= TOL[dtype], f"dW[{l}]"
+            assert_elementwise(host64(gdW[l]), ref_dW[l], dtype, f"dW[{l}]")
     return gdX, ref_dX
 
 
@@ -98,3 +100,13 @@ def test_group_members_must_share_the_buffer_and_the_width(ctx):
         tf.tf_stage_backward_shared(ctx, [(256, 256)] * 2, 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, [0, 0], [A, B], [A, A], tf.TF_BF16)
     with pytest.raises(tf.TfError):
         tf.tf_stage_backward_shared(ctx, [(256, 256), (128, 256)], 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, [0, 0], [A, A], [A, A], tf.TF_BF16)
+
+
+def test_a_group_that_would_straddle_the_launch_limit_moves_to_the_next_launch(ctx):
+    """24 groups of three layers each: 21 groups fill 63 of the 64 descriptors of a launch, the
+    22nd does not fit in what is left and must open the next launch whole (a contraction cannot
+    continue across launches).  One block of rows frozen nowhere: every layer is checked."""
+    shapes = [(256, 256), (256, 512), (256, 256)] * 24
+    groups = [g for g in range(24) for _ in range(3)]
+    fm = np.zeros(72, np.uint8); fm[[1, 40, 71]] = 1
+    _run(ctx, shapes, groups, 256, "bf16", fm, seed=6)
