@@ -10,8 +10,11 @@
  *     no update; update rule Delta_t = (1/M) sum_m U_{t,m} (.) g_{t,m}) with
  *     the AdamW optimizer named in Table exp_setup;
  *   - the APF stability recurrences and score of Sec. 2.3.
- * The freeze ratio r and the freeze masks are inputs; the schedule DAG and the
- * linear program that produce r are not part of this library.
+ * To those three the freeze ratio r and the freeze masks are inputs.  The steps
+ * that produce them are offered beside the hot path: the metric-aware selection
+ * statistics (APF scores, AutoFreeze norms, the budget reconciliation of Alg. 2,
+ * row-block draws) and, host only, the schedule DAG, its longest paths and the
+ * linear program of Sec. 3.2 that turns measured action times into ratios.
  *
  * General conventions
  *   - Every function returns an int: TF_OK (0) or a negative tf_status.
@@ -27,8 +30,11 @@
  *   - All argument validation happens before the first HIP call of a function,
  *     so argument errors are reported identically on a machine without a GPU.
  *   - Device pointers must be 16-byte aligned (TF_ERR_ALIGN otherwise).
- *   - Inputs may alias each other (q/k/v may share one X).  Outputs must not
- *     alias anything else.
+ *   - Inputs may alias each other (q/k/v may share one X).  An output must not
+ *     overlap any input or any other output of the same call, with one
+ *     exception: the members of an input group of tf_stage_backward_shared pass
+ *     the same dX pointer.  The stage-backward entry points check this on the
+ *     host (byte ranges from the shapes) and return TF_ERR_ALIAS.
  *   - A tf_ctx serves one stream at a time and is not re-entrant.
  *   - Matrices are dense row-major with no padding.  A linear layer l has
  *     K_l input features and N_l output features, forward Y_l = X_l W_l with
@@ -58,13 +64,17 @@ typedef enum {
     TF_ERR_ALIGN       = -4,   /* a device pointer is not 16-byte aligned */
     TF_ERR_WORKSPACE   = -5,   /* internal staging could not be allocated */
     TF_ERR_HIP         = -6,   /* a HIP call failed; see tf_last_hip_error */
-    TF_ERR_NO_DEVICE   = -7    /* tf_create: no usable gfx950 device with that id */
+    TF_ERR_NO_DEVICE   = -7,   /* tf_create: no usable gfx950 device with that id */
+    TF_ERR_ALIAS       = -8    /* an output overlaps an input or another output of the call */
 } tf_status;
 
 /* Create / destroy a context bound to HIP device `device_id`.  tf_create makes
  * that device current for the calling thread and queries its properties; it
  * fails with TF_ERR_NO_DEVICE when there is no such device.  The context owns
- * only small internal bookkeeping; no per-call allocation happens later. */
+ * its host-side bookkeeping (timing events) and ONE device allocation, made here:
+ * the 8.2 KB rank-search state of tf_reconcile_mask (TF_ERR_WORKSPACE if that
+ * fails).  No call allocates device memory afterwards.  Every later call on the
+ * context makes device_id current for the calling thread before it launches. */
 int tf_create(tf_ctx** out, int device_id);
 int tf_destroy(tf_ctx* ctx);
 

@@ -26,7 +26,11 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "tf_oracle.c")
-_LIB = os.path.join(_HERE, "libtf_oracle.so")
+# TF_ORACLE_SANITIZE=1 in the environment: the same source built with AddressSanitizer and
+# UndefinedBehaviorSanitizer into a library of its own (the process must then have the ASan
+# runtime preloaded; tests/test_oracle_sanitized.py runs the pins that way).
+_SANITIZE = os.environ.get("TF_ORACLE_SANITIZE", "") == "1"
+_LIB = os.path.join(_HERE, "libtf_oracle_san.so" if _SANITIZE else "libtf_oracle.so")
 
 _lib = None
 
@@ -34,8 +38,10 @@ _lib = None
 def build(force: bool = False) -> str:
     """Compile tf_oracle.c with gcc (no fast-math, no contraction)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
-               "-std=c11", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        opt = (["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
+               if _SANITIZE else ["-O2"])
+        cmd = ["gcc"] + opt + ["-fopenmp", "-ffp-contract=off", "-fPIC", "-shared",
+                               "-std=c11", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 

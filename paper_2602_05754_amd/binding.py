@@ -137,6 +137,15 @@ def _dptr(x) -> Optional[int]:
     return int(x.data_ptr())
 
 
+_DTYPE_NAME = {TF_F32: "torch.float32", TF_BF16: "torch.bfloat16"}
+_DTYPE_CODE = {v: k for k, v in _DTYPE_NAME.items()}
+
+
+def _device_index(x) -> int:
+    """Device index of a tensor on a GPU, -1 for a host tensor."""
+    return int(x.device.index or 0) if x.is_cuda else -1
+
+
 class PtrTable:
     """A list of device buffers marshalled once: the host array of their pointers and their
     sizes in bytes.  Pass it wherever a wrapper takes a list of tensors when the same list is
@@ -148,12 +157,16 @@ class PtrTable:
         n = len(self._items)
         self.arr = (ctypes.c_void_p * max(n, 1))()
         self.nbytes = np.full(n, np.iinfo(np.int64).max, dtype=np.int64)     # raw ints: size unknown
+        self.dtype_code = np.full(n, -2, dtype=np.int64)                     # -2 unknown (raw int), -1 neither f32 nor bf16
+        self.device = np.full(n, -2, dtype=np.int64)                         # -2 unknown, -1 host
         for i, x in enumerate(self._items):
             self.arr[i] = _dptr(x)
             if x is not None and not isinstance(x, int):
                 if not x.is_contiguous():
                     raise ValueError(f"entry {i}: tensor must be contiguous")
                 self.nbytes[i] = x.numel() * x.element_size()
+                self.dtype_code[i] = _DTYPE_CODE.get(str(x.dtype), -1)
+                self.device[i] = _device_index(x)
         self.present = np.array([x is not None for x in self._items], dtype=bool)
         self.ptr = ctypes.cast(self.arr, ctypes.c_void_p)
 
@@ -199,10 +212,15 @@ def _stream_handle(stream) -> Optional[int]:
 _ELEM_SIZE = {TF_F32: 4, TF_BF16: 2}
 
 
-def _check_numel(x, numel, dtype_code, what):
-    """Host-side guard: a tensor handed to a kernel must hold what the kernel will index."""
+def _check_numel(x, numel, dtype_code, what, ctx=None):
+    """Host-side guard: a tensor handed to a kernel must hold what the kernel will index, in the
+    element type the call names, on the device of the context (raw integers pass unchecked)."""
     if x is None or isinstance(x, int):
         return
+    if str(x.dtype) != _DTYPE_NAME[dtype_code]:
+        raise ValueError(f"{what}: tensor of {x.dtype} where the call says {_DTYPE_NAME[dtype_code]}")
+    if ctx is not None and _device_index(x) != ctx.device_id:
+        raise ValueError(f"{what}: tensor on {x.device}, the context is bound to GPU {ctx.device_id}")
     if x.numel() * x.element_size() < numel * _ELEM_SIZE[dtype_code]:
         raise ValueError(f"{what}: buffer of {x.numel() * x.element_size()} bytes is smaller than "
                          f"{numel} elements of {_ELEM_SIZE[dtype_code]} bytes")
@@ -210,24 +228,34 @@ def _check_numel(x, numel, dtype_code, what):
         raise ValueError(f"{what}: tensor must be contiguous")
 
 
-def _check_seq(seq, numels, dtype_code, what, skip=None):
+def _check_seq(seq, numels, dtype_code, what, skip=None, ctx=None):
     """_check_numel over a list of buffers; entries with skip[i] set are not looked at."""
     if seq is None:
         return
     if isinstance(seq, PtrTable):
         need = np.asarray(numels, dtype=np.int64) * _ELEM_SIZE[dtype_code]
-        bad = seq.present & (seq.nbytes < need)
+        look = seq.present.copy()
         if skip is not None:
-            bad &= ~np.asarray(skip, dtype=bool)
+            look &= ~np.asarray(skip, dtype=bool)
+        bad = look & (seq.nbytes < need)
         if bad.any():
             i = int(np.flatnonzero(bad)[0])
             raise ValueError(f"{what}[{i}]: buffer of {int(seq.nbytes[i])} bytes is smaller than "
                              f"{int(numels[i])} elements of {_ELEM_SIZE[dtype_code]} bytes")
+        bad = look & (seq.dtype_code != -2) & (seq.dtype_code != dtype_code)
+        if bad.any():
+            i = int(np.flatnonzero(bad)[0])
+            raise ValueError(f"{what}[{i}]: tensor of {seq[i].dtype} where the call says {_DTYPE_NAME[dtype_code]}")
+        if ctx is not None:
+            bad = look & (seq.device != -2) & (seq.device != ctx.device_id)
+            if bad.any():
+                i = int(np.flatnonzero(bad)[0])
+                raise ValueError(f"{what}[{i}]: tensor on {seq[i].device}, the context is bound to GPU {ctx.device_id}")
         return
     for i, x in enumerate(seq):
         if skip is not None and skip[i]:
             continue
-        _check_numel(x, int(numels[i]), dtype_code, f"{what}[{i}]")
+        _check_numel(x, int(numels[i]), dtype_code, f"{what}[{i}]", ctx)
 
 
 class Context:
@@ -307,11 +335,11 @@ def tf_stage_backward(ctx, shapes: Sequence[tuple], T: int, io_dtype: int,
     L = len(shapes)
     sh = np.ascontiguousarray(np.asarray(shapes, dtype=np.int64).reshape(L, 2))
     fm, fm_p = _host(freeze_mask, np.uint8, L)
-    _check_seq(W, sh[:, 0] * sh[:, 1], io_dtype, "W")
-    _check_seq(dY, T * sh[:, 1], io_dtype, "dY")
-    _check_seq(dX, T * sh[:, 0], io_dtype, "dX")
-    _check_seq(X, T * sh[:, 0], io_dtype, "X", fm)
-    _check_seq(dW, sh[:, 0] * sh[:, 1], dw_dtype, "dW", fm)
+    _check_seq(W, sh[:, 0] * sh[:, 1], io_dtype, "W", ctx=ctx)
+    _check_seq(dY, T * sh[:, 1], io_dtype, "dY", ctx=ctx)
+    _check_seq(dX, T * sh[:, 0], io_dtype, "dX", ctx=ctx)
+    _check_seq(X, T * sh[:, 0], io_dtype, "X", fm, ctx=ctx)
+    _check_seq(dW, sh[:, 0] * sh[:, 1], dw_dtype, "dW", fm, ctx=ctx)
     kW, pW = _ptr_array(W, L)
     kX, pX = _ptr_array(X, L)
     kdY, pdY = _ptr_array(dY, L)
@@ -338,7 +366,7 @@ def tf_masked_adamw(ctx, numel: Sequence[int], p_master, m, v, grad, grad_dtype:
     for name, seq, dt in (("p", p_master, TF_F32), ("m", m, TF_F32), ("v", v, TF_F32),
                           ("grad", grad, grad_dtype), ("p_lowp", p_lowp, TF_BF16),
                           ("ema", ema, TF_F32), ("ema_abs", ema_abs, TF_F32)):
-        _check_seq(seq, ne, dt, name, fm)
+        _check_seq(seq, ne, dt, name, fm, ctx=ctx)
     for i in range(n if elem_freeze_bits is not None else 0):
         if fm is not None and fm[i]:
             continue
@@ -371,7 +399,7 @@ def tf_stability_update(ctx, numel: Sequence[int], delta, ema, ema_abs, ema_deca
             continue
         for name, seq in (("delta", delta), ("ema", ema), ("ema_abs", ema_abs)):
             if seq is not None:
-                _check_numel(seq[i], int(ne[i]), TF_F32, f"{name}[{i}]")
+                _check_numel(seq[i], int(ne[i]), TF_F32, f"{name}[{i}]", ctx)
     keep = [_ptr_array(s, n) for s in (delta, ema, ema_abs, elem_freeze_bits)]
     pp = [k[1] for k in keep]
     rc = lib.tf_stability_update(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
@@ -417,7 +445,7 @@ def tf_autofreeze_norms(ctx, numel: Sequence[int], p_master, snapshot, sq_norms,
             continue
         for name, seq in (("p_master", p_master), ("snapshot", snapshot)):
             if seq is not None:
-                _check_numel(seq[i], int(ne[i]), TF_F32, f"{name}[{i}]")
+                _check_numel(seq[i], int(ne[i]), TF_F32, f"{name}[{i}]", ctx)
     keep = [_ptr_array(s, n) for s in (p_master, snapshot)]
     rc = lib.tf_autofreeze_norms(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
                                  n, ne_p, keep[0][1], keep[1][1], fm_p, int(bool(update_snapshot)), _dptr(sq_norms))
@@ -498,12 +526,12 @@ def tf_stage_backward_blocks(ctx, shapes: Sequence[tuple], T: int, io_dtype: int
     for l in range(L):
         K, N = int(sh[l, 0]), int(sh[l, 1])
         frozen = fm is not None and fm[l]
-        if W is not None: _check_numel(W[l], K * N, io_dtype, f"W[{l}]")
-        if dY is not None: _check_numel(dY[l], T * N, io_dtype, f"dY[{l}]")
-        if dX is not None: _check_numel(dX[l], T * K, io_dtype, f"dX[{l}]")
+        if W is not None: _check_numel(W[l], K * N, io_dtype, f"W[{l}]", ctx)
+        if dY is not None: _check_numel(dY[l], T * N, io_dtype, f"dY[{l}]", ctx)
+        if dX is not None: _check_numel(dX[l], T * K, io_dtype, f"dX[{l}]", ctx)
         if not frozen:
-            if X is not None: _check_numel(X[l], T * K, io_dtype, f"X[{l}]")
-            if dW is not None: _check_numel(dW[l], K * N, dw_dtype, f"dW[{l}]")
+            if X is not None: _check_numel(X[l], T * K, io_dtype, f"X[{l}]", ctx)
+            if dW is not None: _check_numel(dW[l], K * N, dw_dtype, f"dW[{l}]", ctx)
     keep = [_ptr_array(s, L) for s in (W, X, dY, dX, dW)]
     rm_keep, rm_p = _host_mask_table(row_block_mask, [tuple(map(int, r)) for r in sh], int(block_rows))
     rc = lib.tf_stage_backward_blocks(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
@@ -526,12 +554,12 @@ def tf_stage_backward_shared(ctx, shapes: Sequence[tuple], T: int, io_dtype: int
     for l in range(L):
         K, N = int(sh[l, 0]), int(sh[l, 1])
         frozen = fm is not None and fm[l]
-        if W is not None: _check_numel(W[l], K * N, io_dtype, f"W[{l}]")
-        if dY is not None: _check_numel(dY[l], T * N, io_dtype, f"dY[{l}]")
-        if dX is not None: _check_numel(dX[l], T * K, io_dtype, f"dX[{l}]")
+        if W is not None: _check_numel(W[l], K * N, io_dtype, f"W[{l}]", ctx)
+        if dY is not None: _check_numel(dY[l], T * N, io_dtype, f"dY[{l}]", ctx)
+        if dX is not None: _check_numel(dX[l], T * K, io_dtype, f"dX[{l}]", ctx)
         if not frozen:
-            if X is not None: _check_numel(X[l], T * K, io_dtype, f"X[{l}]")
-            if dW is not None: _check_numel(dW[l], K * N, dw_dtype, f"dW[{l}]")
+            if X is not None: _check_numel(X[l], T * K, io_dtype, f"X[{l}]", ctx)
+            if dW is not None: _check_numel(dW[l], K * N, dw_dtype, f"dW[{l}]", ctx)
     keep = [_ptr_array(s, L) for s in (W, X, dY, dX, dW)]
     rm_keep, rm_p = _host_mask_table(row_block_mask, [tuple(map(int, r)) for r in sh], int(block_rows))
     rc = lib.tf_stage_backward_shared(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,

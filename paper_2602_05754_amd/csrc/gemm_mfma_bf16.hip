@@ -60,6 +60,8 @@ constexpr int kGroupM = 8;                            // tile rows per L2 locali
 constexpr int kXcds = 8;
 constexpr int kXcdRun = 32;                           // consecutive logical tiles kept on one XCD
 
+static_assert(sizeof(GemmBatch) <= 4160, "the batch travels by value in the kernel-argument segment");
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -91,10 +93,11 @@ __device__ __forceinline__ float acc_read(float a) {
 // multiple of 8 whenever a workgroup gets more than one tile).  Runs of kXcdRun consecutive
 // logical tiles are kept on one XCD (shared L2), runs go round-robin over the XCDs so that
 // all of them work on the same part of the tile list.
-__device__ __forceinline__ int logical_tile(int b, int nb) {
+// A grid that is not a multiple of 8 (fewer than 8 compute units) keeps the plain order.
+__host__ __device__ __forceinline__ int logical_tile(int b, int nb, int grid) {
     const int span = kXcds * kXcdRun;
     const int full = (nb / span) * span;
-    if (b >= full) return b;
+    if (b >= full || grid % kXcds != 0) return b;
     const int xcd = b % kXcds, idx = b / kXcds;
     return ((idx / kXcdRun) * kXcds + xcd) * kXcdRun + idx % kXcdRun;
 }
@@ -192,13 +195,14 @@ __device__ __forceinline__ Run make_run(const GemmProblem& P, int m0, int n0) {
 // halves of one of its own 64-bit scalar additions (s_add_u32 / s_addc_u32) unless it is told:
 // a clobbered carry sends the high word of a global address off by one as soon as the addition
 // crosses a 4 GiB boundary.  Hence the "scc" clobber; the build scans the generated code for
-// inline assembly between a producer and a consumer of SCC and refuses it.
+// inline assembly between a producer and a consumer of SCC and refuses it.  M0 is named for the
+// same reason: the compiler keeps values of its own there (LDS-DMA builtins, lane selects).
 template <int kLdsOff>
 __device__ __forceinline__ void direct_load_16B(const char* gbase, uint32_t voff, uint32_t lds_wave_base) {
     asm volatile("s_add_u32 m0, %0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :
                  : "s"(lds_wave_base), "v"(voff), "s"(gbase), "n"(kLdsOff)
-                 : "memory", "scc");
+                 : "memory", "scc", "m0");
 }
 __device__ __forceinline__ void wait_direct_loads() {
     __builtin_amdgcn_s_waitcnt(0x0f70);     // vmcnt(0), other counters untouched
@@ -238,7 +242,7 @@ struct StreamPos {             // identifies the run held in `nxt`
 
 template <bool kTN>
 __device__ __forceinline__ Run stream_first(StreamPos& c, const GemmBatch& batch, int vb) {
-    const TilePos tp = locate_tile(batch, logical_tile(vb, batch.total_tiles), c.pi);
+    const TilePos tp = locate_tile(batch, logical_tile(vb, batch.total_tiles, int(gridDim.x)), c.pi);
     c.vb = vb; c.pi = tp.pi; c.m0 = tp.m0; c.n0 = tp.n0;
     c.seg = 0; c.n_seg = batch.p[tp.pi].n_seg;
     return make_run<kTN>(batch.p[c.pi], c.m0, c.n0);
@@ -555,7 +559,7 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
 
     // The tile being consumed.
     int cvb = int(blockIdx.x);
-    TilePos ct = locate_tile(batch, logical_tile(cvb, total), 0);
+    TilePos ct = locate_tile(batch, logical_tile(cvb, total, stride), 0);
 
     // Stage offsets (bytes from the start of LDS): d0 / s0 hold the step being consumed, d1 / s1
     // the next one, d2 is the deep stage that this step's first quarter fills.
@@ -708,15 +712,21 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
         cvb += stride;
         if (cvb >= total) break;
         __syncthreads();          // no wave may fill that stage while another still turns its block around in it
-        ct = locate_tile(batch, logical_tile(cvb, total), ct.pi);
+        ct = locate_tile(batch, logical_tile(cvb, total, stride), ct.pi);
     }
     wait_direct_loads();      // nothing of this workgroup may still be in flight towards LDS
 }
 
-int compute_units() {
-    static int cached[64] = {0};
+constexpr int kMaxDevices = 64;
+
+int current_device() {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 256;
+    return (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) ? dev : -1;
+}
+
+int compute_units(int dev) {
+    static int cached[kMaxDevices] = {0};
+    if (dev < 0) return 256;
     if (cached[dev] == 0) {
         int n = 0;
         if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
@@ -728,18 +738,46 @@ int compute_units() {
 template <bool kTN, bool kOutBf16, bool kAccumulate>
 hipError_t launch_one(hipStream_t stream, const GemmBatch& batch) {
     auto kern = gemm_mfma_kernel<kTN, kOutBf16, kAccumulate>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-    if (e != hipSuccess) return e;
-    // one workgroup per compute unit (a workgroup takes all of a unit's LDS and registers)
-    const int grid = batch.total_tiles < compute_units() ? batch.total_tiles : compute_units();
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(kThreads), kLdsBytes, stream, batch);
+    // the 160 KB of dynamic LDS are allowed once per kernel instantiation and device
+    static bool lds_allowed[kMaxDevices] = {false};
+    const int dev = current_device();
+    if (dev < 0 || !lds_allowed[dev]) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        if (dev >= 0) lds_allowed[dev] = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(persistent_grid(batch.total_tiles, compute_units(dev))), dim3(kThreads), kLdsBytes,
+                       stream, batch);
     return hipGetLastError();
 }
 
 }  // namespace
 
+// One workgroup per compute unit (a workgroup takes all of a unit's LDS and registers).  When a
+// workgroup gets more than one tile the grid is a multiple of the XCD count: the tiles b,
+// b + grid, ... of a workgroup then keep b % 8, and with it both the XCD and the increasing
+// order of logical tiles that the problem search relies on.
+int persistent_grid(int total_tiles, int units) {
+    if (total_tiles <= units) return total_tiles;
+    const int g = units - units % kXcds;
+    return g > 0 ? g : units;
+}
+
 int gemm_mfma_tile() { return kBM; }
+
+}  // namespace tf
+
+// Test hook (not part of the public header): the order in which a launch of total_tiles tiles on
+// `units` compute units walks its tiles.  out[b] = logical tile of virtual block b; returns the
+// number of workgroups (workgroup w takes the virtual blocks w, w + grid, ...).
+extern "C" int tf_internal_tile_order(int total_tiles, int units, int32_t* out) {
+    const int grid = tf::persistent_grid(total_tiles, units);
+    for (int b = 0; b < total_tiles; ++b) out[b] = tf::logical_tile(b, total_tiles, grid);
+    return grid;
+}
+
+namespace tf {
 
 bool mfma_shape_ok(int64_t M, int64_t N, int64_t Kc, int64_t lda, int64_t ldb) {
     // 16-byte direct loads: row pitches must keep every row 16-byte aligned

@@ -141,6 +141,27 @@ hipError_t launch_planned(tf_ctx* ctx, hipStream_t stream, std::vector<Planned>&
     return hipSuccess;
 }
 
+// Byte ranges of a stage backward's tensors: an output may overlap neither an input nor
+// another output (inputs may overlap each other).  Sweep over the ranges sorted by start.
+struct ByteRange { uintptr_t lo, hi; bool output; };
+bool outputs_overlap_something(std::vector<ByteRange>& r) {
+    std::sort(r.begin(), r.end(), [](const ByteRange& a, const ByteRange& b) { return a.lo < b.lo; });
+    uintptr_t end_any = 0, end_out = 0;          // furthest end among the ranges seen so far: all / outputs
+    for (const ByteRange& x : r) {
+        if (x.output ? x.lo < end_any : x.lo < end_out) return true;
+        end_any = std::max(end_any, x.hi);
+        if (x.output) end_out = std::max(end_out, x.hi);
+    }
+    return false;
+}
+
+// Later calls may come from another thread, or after the caller made another device current.
+inline bool use_device(tf_ctx* ctx) {
+    const hipError_t e = hipSetDevice(ctx->device_id);
+    if (e != hipSuccess) { ctx->last_hip_error = static_cast<int>(e); return false; }
+    return true;
+}
+
 int validate_elementwise_common(int32_t n_tensors, const int64_t* numel,
                                 void* const* ema, void* const* ema_abs,
                                 const uint8_t* tensor_freeze_mask,
@@ -184,6 +205,7 @@ const char* tf_strerror(int code) {
         case TF_ERR_WORKSPACE: return "workspace allocation failed";
         case TF_ERR_HIP: return "HIP runtime error (see tf_last_hip_error)";
         case TF_ERR_NO_DEVICE: return "no usable gfx950 device";
+        case TF_ERR_ALIAS: return "an output buffer overlaps an input or another output";
         default: return "unknown status code";
     }
 }
@@ -301,12 +323,36 @@ int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
             }
         }
     }
+    const int64_t in_size = io_dtype == TF_BF16 ? 2 : 4, dw_size = dw_dtype == TF_BF16 ? 2 : 4;
+    if (n_layers > 0) {
+        // no output may overlap an input or another output (the members of an input group pass
+        // one dX buffer: it is listed once, for the member that leads the group)
+        std::vector<ByteRange> ranges;
+        ranges.reserve(size_t(n_layers) * 5);
+        auto add = [&](const void* p, int64_t elems, int64_t size, bool output) {
+            const uintptr_t lo = reinterpret_cast<uintptr_t>(p);
+            ranges.push_back(ByteRange{lo, lo + uintptr_t(elems) * uintptr_t(size), output});
+        };
+        std::vector<uint8_t> group_seen(input_group ? n_layers : 0, 0);
+        for (int32_t l = 0; l < n_layers; ++l) {
+            const int64_t K = shapes[l].K, N = shapes[l].N;
+            add(W[l], K * N, in_size, false);
+            add(dY[l], T * N, in_size, false);
+            const int32_t g = input_group ? input_group[l] : -1;
+            if (g < 0 || !group_seen[g]) add(dX[l], T * K, in_size, true);
+            if (g >= 0) group_seen[g] = 1;
+            if (freeze_mask && freeze_mask[l]) continue;
+            add(X[l], T * K, in_size, false);
+            add(dW[l], K * N, dw_size, true);
+        }
+        if (outputs_overlap_something(ranges)) return TF_ERR_ALIAS;
+    }
     if (!ctx) return TF_ERR_INVALID_ARG;
     if (n_layers == 0) return TF_OK;
+    if (!use_device(ctx)) return TF_ERR_HIP;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const Dtype in_dt = to_dtype(io_dtype);
-    const int64_t in_size = io_dtype == TF_BF16 ? 2 : 4, dw_size = dw_dtype == TF_BF16 ? 2 : 4;
 
     // input gradients: every layer, whatever the masks say.  Layers that share their input are
     // segments of one problem: their products are summed in the accumulators and rounded once.
@@ -447,6 +493,7 @@ int tf_masked_adamw(tf_ctx* ctx, void* hip_stream,
     }
     if (!ctx) return TF_ERR_INVALID_ARG;
     if (n_tensors == 0) return TF_OK;
+    if (!use_device(ctx)) return TF_ERR_HIP;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     AdamwParams hp;
@@ -520,6 +567,7 @@ int tf_stability_update(tf_ctx* ctx, void* hip_stream,
     }
     if (!ctx) return TF_ERR_INVALID_ARG;
     if (n_tensors == 0) return TF_OK;
+    if (!use_device(ctx)) return TF_ERR_HIP;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     AdamwParams hp;
@@ -613,6 +661,7 @@ int tf_autofreeze_norms(tf_ctx* ctx, void* hip_stream,
     }
     if (!ctx) return TF_ERR_INVALID_ARG;
     if (n_tensors == 0) return TF_OK;
+    if (!use_device(ctx)) return TF_ERR_HIP;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int64_t epb = norm_elems_per_block();
@@ -698,6 +747,7 @@ int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
     }
     if (n_freeze > total) return TF_ERR_INVALID_ARG;
     if (!ctx) return TF_ERR_INVALID_ARG;
+    if (!use_device(ctx)) return TF_ERR_HIP;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const RcKeys keys = perm32_keys(seed);
@@ -785,6 +835,7 @@ int tf_row_blocks_to_bits(tf_ctx* ctx, void* hip_stream,
         }
     }
     if (!ctx) return TF_ERR_INVALID_ARG;
+    if (!use_device(ctx)) return TF_ERR_HIP;
 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     FillBatch batch;

@@ -42,7 +42,7 @@ struct GemmProblem {
 
 constexpr int kMaxProblemsPerLaunch = 64;
 
-struct GemmBatch {          // passed by value as the kernel argument (< 4 KB)
+struct GemmBatch {          // passed by value as the kernel argument (64 x 64 B + 8 B = 4104 B)
     GemmProblem p[kMaxProblemsPerLaunch];
     int32_t n_problems;
     int32_t total_tiles;
@@ -60,6 +60,7 @@ hipError_t launch_gemm_mfma_bf16(hipStream_t stream, GemmBatch& batch, int n_pro
                                  Layout layout, Dtype out_dtype, bool accumulate);
 int gemm_generic_tile();          // tile edge of the generic kernel (square)
 int gemm_mfma_tile();             // tile edge of the MFMA kernel (square)
+int persistent_grid(int total_tiles, int units);    // workgroups of an MFMA launch on `units` compute units
 
 // ---------------------------------------------------------------------------
 // Fused elementwise pass: masked AdamW (+ APF EMAs) or the stand-alone EMA

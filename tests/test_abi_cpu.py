@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, n) is not None, n
     assert sorted(tf.EXPORTED_SYMBOLS) == names
     assert re.match(r"^\d+\.\d+\.\d+$", tf.tf_version())
-    for code in range(-7, 1):
+    for code in range(-8, 1):
         assert tf.tf_strerror(code) and tf.tf_strerror(code) != "unknown status code"
     assert tf.tf_strerror(-99) == "unknown status code"
 
@@ -57,7 +57,7 @@ def _code(fn, *a, **k):
 def test_stage_backward_validation_precedes_any_gpu_work():
     A = 4096  # fake, 16-byte aligned "device pointers": never dereferenced, validation fails first
     sh = [(8, 8)]
-    ok = dict(W=[A], X=[A], dY=[A], freeze_mask=[0], dX=[A], dW=[A])
+    ok = dict(W=[A], X=[2 * A], dY=[3 * A], freeze_mask=[0], dX=[4 * A], dW=[5 * A])
     call = lambda **kw: _code(tf.tf_stage_backward, None, kw.pop("shapes", sh), kw.pop("T", 4),
                               kw.pop("io", tf.TF_F32), kw.pop("W", ok["W"]), kw.pop("X", ok["X"]),
                               kw.pop("dY", ok["dY"]), kw.pop("fm", ok["freeze_mask"]), kw.pop("dX", ok["dX"]),
@@ -67,12 +67,49 @@ def test_stage_backward_validation_precedes_any_gpu_work():
     assert call(io=7) == -3 and call(dwt=5) == -3
     assert call(io=tf.TF_BF16, dwt=tf.TF_BF16, acc=True) == -3     # accumulate needs fp32 dW
     assert call(io=tf.TF_F32, dwt=tf.TF_BF16) == -3
-    assert call(W=[A + 2]) == -4 and call(dX=[A + 8]) == -4 and call(dW=[A + 4]) == -4
+    assert call(W=[A + 2]) == -4 and call(dX=[4 * A + 8]) == -4 and call(dW=[5 * A + 4]) == -4
     assert call(W=[None]) == -1 and call(dW=[None]) == -1 and call(X=[None]) == -1
     assert call(fm=[2]) == -1
     # frozen layer: X and dW may be NULL, and are not alignment-checked
     assert call(fm=[1], dW=[None], X=[None]) == -1   # only the NULL ctx is left to complain about
     assert call(fm=[1], dW=[A + 2]) == -1
+    # an output may overlap neither an input nor another output; inputs may overlap each other
+    ALIAS = -8
+    assert call(X=[A], dY=[A]) == -1                 # W, X, dY in one place: allowed
+    assert call(dX=[A]) == ALIAS and call(dW=[3 * A]) == ALIAS and call(dX=[5 * A]) == ALIAS
+    assert call(dX=[2 * A + 4 * 8 * 4 - 16]) == ALIAS            # the last 16 bytes of X
+    assert call(dX=[2 * A + 4 * 8 * 4]) == -1                    # right behind X
+    assert call(fm=[1], dW=[A], X=[None]) == -1      # a frozen layer's dW is not looked at
+    two = dict(shapes=[(8, 8), (8, 8)], W=[A, A], X=[2 * A, 2 * A], dY=[3 * A, 3 * A], fm=[0, 0])
+    assert call(**two, dX=[4 * A, 6 * A], dW=[5 * A, 7 * A]) == -1
+    assert call(**two, dX=[4 * A, 4 * A], dW=[5 * A, 7 * A]) == ALIAS       # two layers, one dX, no group
+    assert call(**two, dX=[4 * A, 6 * A], dW=[5 * A, 5 * A + 16]) == ALIAS
+    shared = lambda dX, groups: _code(tf.tf_stage_backward_shared, None, two["shapes"], 4, tf.TF_F32, two["W"], two["X"],
+                                      two["dY"], [0, 0], None, 0, groups, dX, [5 * A, 7 * A], tf.TF_F32)
+    assert shared([4 * A, 4 * A], [0, 0]) == -1      # members of an input group share their dX
+    assert shared([4 * A, 4 * A], [0, 1]) == ALIAS
+
+
+def test_tile_order_of_a_persistent_launch():
+    """Every logical tile is visited once, and the tiles of one workgroup come in increasing
+    order (the device-side search for a tile's problem only moves forward), for grids that are
+    and are not a multiple of the XCD count."""
+    lib = tf.load_library()
+    fn = lib.tf_internal_tile_order
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.POINTER(ctypes.c_int32)]
+    for units in (256, 304, 250, 7, 8, 1):
+        for total in (1, 5, units - 1, units, units + 1, 511, 512, 513, 1000, 4864, 19456):
+            if total < 1:
+                continue
+            out = (ctypes.c_int32 * total)()
+            grid = fn(total, units, out)
+            order = np.frombuffer(out, dtype=np.int32)
+            assert sorted(order.tolist()) == list(range(total)), (units, total)
+            assert 1 <= grid <= min(total, units) and (total <= units or grid % 8 == 0 or units < 8), (units, total, grid)
+            for w in range(grid):
+                mine = order[w::grid]
+                assert np.all(np.diff(mine) > 0), (units, total, w)
 
 
 def test_adamw_validation_precedes_any_gpu_work():
@@ -222,7 +259,7 @@ def test_row_block_draw_matches_the_oracle_rule():
 def test_row_block_entry_points_validate_before_any_gpu_work():
     A = 4096
     INV, SHAPE, ALIGN = -1, -2, -4
-    ok = dict(W=[A], X=[A], dY=[A], freeze_mask=[0], dX=[A], dW=[A])
+    ok = dict(W=[A], X=[2 * A], dY=[3 * A], freeze_mask=[0], dX=[4 * A], dW=[5 * A])
     call = lambda shapes, masks, br, **kw: _code(tf.tf_stage_backward_blocks, None, shapes, 8, tf.TF_F32,
                                                  kw.get("W", ok["W"]), ok["X"], ok["dY"], ok["freeze_mask"], masks, br,
                                                  ok["dX"], ok["dW"], tf.TF_F32)
@@ -263,3 +300,32 @@ def test_pointer_tables_marshal_once_and_check_sizes():
     with pytest.raises(ValueError):
         tf.tf_masked_adamw(None, [64], tf.PtrTable([mk(63)]), [8192], [8192], [8192], tf.TF_BF16, [1],
                            1e-4, 0.9, 0.95, 1e-8, 0.1)
+
+
+def test_binding_refuses_a_wrong_element_type_or_device():
+    """The wrappers compare each tensor's element type with the type the call names and its
+    device with the context's, lists and pointer tables alike."""
+    import torch
+
+    class Ctx:                       # stands in for a context bound to GPU 0; never reaches the library
+        device_id = 0
+        handle = None
+
+        def last_hip_error(self):
+            return 0
+
+    K, N, T = 8, 8, 4
+    f32 = lambda n: torch.zeros(n, dtype=torch.float32)
+    bf = lambda n: torch.zeros(n, dtype=torch.bfloat16)
+    good = [[f32(K * N)], [f32(T * K)], [f32(T * N)], [f32(T * K)], [f32(K * N)]]
+    call = lambda ctx, io, a: tf.tf_stage_backward(ctx, [(K, N)], T, io, a[0], a[1], a[2], [0], a[3], a[4], tf.TF_F32)
+    for wrap in (list, tf.PtrTable):
+        with pytest.raises(ValueError, match="bfloat16"):
+            call(None, tf.TF_BF16, [wrap(x) for x in good])                  # fp32 tensors, the call says bf16
+        mixed = [wrap(x) for x in good[:2]] + [wrap([bf(2 * T * N)])] + [wrap(x) for x in good[3:]]
+        with pytest.raises(ValueError, match=r"dY\[0\]"):
+            call(None, tf.TF_F32, mixed)
+        with pytest.raises(ValueError, match="GPU 0"):
+            call(Ctx(), tf.TF_F32, [wrap(x) for x in good])                  # host tensors, a context on GPU 0
+    with pytest.raises(ValueError, match="float32"):
+        tf.tf_masked_adamw(None, [64], [bf(128)], [f32(64)], [f32(64)], [bf(64)], tf.TF_BF16, [1], 1e-4, 0.9, 0.95, 1e-8, 0.1)

@@ -153,6 +153,10 @@ def test_degenerate_calls(ctx):
     with pytest.raises(ValueError):     # binding refuses a buffer smaller than the shape says
         tf.tf_stage_backward(ctx, [(512, 512)], 256, tf.TF_BF16, [gdX[0]], [gdX[0]], [gdX[0]], None,
                              [gdX[0]], [gdX[0]], tf.TF_BF16)
+    with pytest.raises(tf.TfError) as ei:     # an output that is also an input is refused before anything runs
+        tf.tf_stage_backward(ctx, [(256, 256)], 256, tf.TF_BF16, [gdX[0]], [gdX[1]], [gdX[2]], None,
+                             [gdX[0]], [gdX[3]], tf.TF_BF16)
+    assert ei.value.code == -8
 
 
 def test_pointer_tables_give_the_same_bytes_as_lists(ctx):

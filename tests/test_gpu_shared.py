@@ -88,18 +88,23 @@ def test_fp32_groups_fall_back_to_one_launch_per_member(ctx):
 def test_bf16_group_with_ragged_shapes_is_refused(ctx):
     shapes, groups = [(256, 688), (256, 688)], [0, 0]      # 688 is not a multiple of the tile edge
     A = torch.zeros(256 * 688 * 2, dtype=torch.bfloat16, device="cuda")
+    G, D1, D2 = (torch.zeros(256 * 688, dtype=torch.bfloat16, device="cuda") for _ in range(3))
     with pytest.raises(tf.TfError) as e:
-        tf.tf_stage_backward_shared(ctx, shapes, 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, groups, [A, A], [A, A], tf.TF_BF16)
+        tf.tf_stage_backward_shared(ctx, shapes, 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, groups, [G, G], [D1, D2], tf.TF_BF16)
     assert e.value.code == -2
 
 
 def test_group_members_must_share_the_buffer_and_the_width(ctx):
-    A = torch.zeros(256 * 256, dtype=torch.bfloat16, device="cuda")
-    B = torch.zeros(256 * 256, dtype=torch.bfloat16, device="cuda")
-    with pytest.raises(tf.TfError):
-        tf.tf_stage_backward_shared(ctx, [(256, 256)] * 2, 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, [0, 0], [A, B], [A, A], tf.TF_BF16)
-    with pytest.raises(tf.TfError):
-        tf.tf_stage_backward_shared(ctx, [(256, 256), (128, 256)], 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, [0, 0], [A, A], [A, A], tf.TF_BF16)
+    A, B, C, D1, D2 = (torch.zeros(256 * 256, dtype=torch.bfloat16, device="cuda") for _ in range(5))
+    with pytest.raises(tf.TfError) as e:
+        tf.tf_stage_backward_shared(ctx, [(256, 256)] * 2, 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, [0, 0], [B, C], [D1, D2], tf.TF_BF16)
+    assert e.value.code == -1
+    with pytest.raises(tf.TfError) as e:
+        tf.tf_stage_backward_shared(ctx, [(256, 256), (128, 256)], 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, [0, 0], [B, B], [D1, D2], tf.TF_BF16)
+    assert e.value.code == -2
+    with pytest.raises(tf.TfError) as e:      # an output that is also an input
+        tf.tf_stage_backward_shared(ctx, [(256, 256)] * 2, 64, tf.TF_BF16, [A, A], [A, A], [A, A], None, None, 0, [0, 0], [B, B], [D1, A], tf.TF_BF16)
+    assert e.value.code == -8
 
 
 def test_a_group_that_would_straddle_the_launch_limit_moves_to_the_next_launch(ctx):
