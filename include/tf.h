@@ -368,6 +368,23 @@ int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
                       int64_t* stats);
 
 /*
+ * tf_reconcile_mask for callers that cannot allocate: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same result, bit for bit.
+ * The call allocates nothing, on the device or on the host, and creates no events (it is not
+ * timed by tf_profile_*): its rank-search state lives in a static device array of 8448 bytes
+ * that is part of the library's code object, one copy per GPU, held until the process ends;
+ * tf_create looks up its address on the context's device.  Limit: as tf_reconcile_mask,
+ * sum(numel) < 2^32 (TF_ERR_SHAPE beyond).  Every call on one GPU, from whatever context or
+ * stream, uses that GPU's one array: the call clears it first with a kernel, and calls that
+ * overlap in time on one GPU race.
+ */
+int tf_reconcile_mask_static(tf_ctx* ctx, void* hip_stream,
+                             int32_t n_tensors, const int64_t* numel,
+                             uint32_t* const* elem_bits,
+                             int64_t n_freeze, uint64_t seed,
+                             int64_t* stats);
+
+/*
  * From measured action times to freeze ratios (Sec. 3.2), host only.
  *
  * Nodes: action (a, m, s) - a = 0 forward / 1 backward, microbatch m in [0, M),

@@ -22,6 +22,7 @@ EXPORTED_SYMBOLS = [
     "tf_stability_scores", "tf_select_lowest", "tf_num_frozen",
     "tf_profile_enable", "tf_profile_collect",
     "tf_autofreeze_norms", "tf_autofreeze_scores", "tf_autofreeze_select", "tf_reconcile_mask",
+    "tf_reconcile_mask_static",
     "tf_stage_backward_blocks", "tf_stage_backward_shared", "tf_select_row_blocks", "tf_row_blocks_to_bits",
     "tf_pipeline_dag", "tf_dag_start_times", "tf_freeze_ratio_lp", "tf_actual_freeze_ratio",
 ]
@@ -113,6 +114,8 @@ def load_library():
     lib.tf_actual_freeze_ratio.argtypes = [f64, i64, i64, i64]
     lib.tf_reconcile_mask.restype = ctypes.c_int
     lib.tf_reconcile_mask.argtypes = [vp, vp, i32, vp, vp, i64, ctypes.c_uint64, vp]
+    lib.tf_reconcile_mask_static.restype = ctypes.c_int
+    lib.tf_reconcile_mask_static.argtypes = [vp, vp, i32, vp, vp, i64, ctypes.c_uint64, vp]
     _lib = lib
     return lib
 
@@ -475,7 +478,13 @@ def tf_autofreeze_select(scores, n_already_frozen: int, percentile: float) -> np
     return out[: s.size]
 
 
-def tf_reconcile_mask(ctx, numel: Sequence[int], elem_bits, n_freeze: int, seed: int, stats=None, stream=None) -> None:
+def tf_reconcile_mask_static(ctx, numel: Sequence[int], elem_bits, n_freeze: int, seed: int, stats=None, stream=None) -> None:
+    """tf_reconcile_mask without any allocation (state in a static device array).  See include/tf.h."""
+    tf_reconcile_mask(ctx, numel, elem_bits, n_freeze, seed, stats, stream, _entry="tf_reconcile_mask_static")
+
+
+def tf_reconcile_mask(ctx, numel: Sequence[int], elem_bits, n_freeze: int, seed: int, stats=None, stream=None,
+                      _entry: str = "tf_reconcile_mask") -> None:
     """Bring the element masks (device uint32 words, updated in place) to exactly n_freeze ones.  See include/tf.h."""
     lib = load_library()
     n = len(numel)
@@ -487,9 +496,9 @@ def tf_reconcile_mask(ctx, numel: Sequence[int], elem_bits, n_freeze: int, seed:
     if stats is not None and not isinstance(stats, int) and stats.numel() * stats.element_size() < 24:
         raise ValueError("stats: needs room for 3 int64 values")
     keep = _ptr_array(elem_bits, n)
-    rc = lib.tf_reconcile_mask(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
-                               n, ne_p, keep[1], int(n_freeze), int(seed) & ((1 << 64) - 1), _dptr(stats))
-    _raise(ctx, rc, "tf_reconcile_mask")
+    rc = getattr(lib, _entry)(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
+                              n, ne_p, keep[1], int(n_freeze), int(seed) & ((1 << 64) - 1), _dptr(stats))
+    _raise(ctx, rc, _entry)
 
 
 def _host_mask_table(row_masks, shapes, block_rows):

@@ -22,11 +22,36 @@ struct tf_ctx {
     std::vector<tf_prof_rec> recs;      // events recorded since the last tf_profile_collect
     std::vector<hipEvent_t> pool;       // events ready for reuse
     tf::RcState* rc_state;              // device memory of tf_reconcile_mask (radix-select state)
+    tf::RcState* rc_state_static;       // this device's static scratch array (tf_reconcile_mask_static)
 };
+
+// Device memory of tf_reconcile_mask_static: one array per GPU, part of the loaded code object,
+// alive until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels get the address that call returned for the current device.
+constexpr size_t kStaticScratchBytes = 8448;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static_assert(sizeof(tf::RcState) <= kStaticScratchBytes, "the rank-search state must fit the static scratch array");
 
 namespace {
 
 using namespace tf;
+
+constexpr int kMaxDevices = 64;
+void* g_scratch_addr[kMaxDevices] = {nullptr};      // address of `scratch` on each device, set by tf_create
+
+// With `device` current: the address of this device's copy of `scratch` (asked for once per device).
+hipError_t static_scratch_address(int device, void** out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (!g_scratch_addr[device]) {
+        void* ptr = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!ptr) return hipErrorInvalidSymbol;
+        g_scratch_addr[device] = ptr;
+    }
+    *out = g_scratch_addr[device];
+    return hipSuccess;
+}
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline bool valid_dtype(int d) { return d == TF_F32 || d == TF_BF16; }
@@ -225,10 +250,18 @@ int tf_create(tf_ctx** out, int device_id) {
     ctx->last_hip_error = 0;
     ctx->profiling = false;
     ctx->rc_state = nullptr;
+    ctx->rc_state_static = nullptr;
     if (hipMalloc(reinterpret_cast<void**>(&ctx->rc_state), tf::rc_state_bytes()) != hipSuccess) {
         delete ctx;
         return TF_ERR_WORKSPACE;
     }
+    void* st = nullptr;
+    if (static_scratch_address(device_id, &st) != hipSuccess) {      // device_id is current here
+        (void)hipFree(ctx->rc_state);
+        delete ctx;
+        return TF_ERR_WORKSPACE;
+    }
+    ctx->rc_state_static = static_cast<tf::RcState*>(st);
     *out = ctx;
     return TF_OK;
 }
@@ -729,11 +762,9 @@ int tf_autofreeze_select(const double* scores, int32_t n, int32_t n_already_froz
     return TF_OK;
 }
 
-int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
-                      int32_t n_tensors, const int64_t* numel,
-                      uint32_t* const* elem_bits,
-                      int64_t n_freeze, uint64_t seed,
-                      int64_t* stats) {
+// Validation shared by the two reconciliation entry points (no HIP call).
+static int validate_reconcile(int32_t n_tensors, const int64_t* numel, uint32_t* const* elem_bits,
+                              int64_t n_freeze, const int64_t* stats) {
     if (n_tensors < 0 || n_freeze < 0) return TF_ERR_INVALID_ARG;
     if (n_tensors > 0 && (!numel || !elem_bits)) return TF_ERR_INVALID_ARG;
     if (stats && (reinterpret_cast<uintptr_t>(stats) & 7u)) return TF_ERR_ALIGN;
@@ -746,15 +777,18 @@ int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
         if (reinterpret_cast<uintptr_t>(elem_bits[i]) & 3u) return TF_ERR_ALIGN;
     }
     if (n_freeze > total) return TF_ERR_INVALID_ARG;
-    if (!ctx) return TF_ERR_INVALID_ARG;
-    if (!use_device(ctx)) return TF_ERR_HIP;
+    return TF_OK;
+}
 
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+// The passes of the reconciliation on the state `st`.  Allocates nothing, on the host or on the
+// device: the tensor descriptors of a launch are built on the stack, pass after pass.
+static hipError_t reconcile_passes(hipStream_t stream, int32_t n_tensors, const int64_t* numel,
+                                   uint32_t* const* elem_bits, int64_t n_freeze, uint64_t seed,
+                                   int64_t* stats, RcState* st) {
     const RcKeys keys = perm32_keys(seed);
-
     const int64_t epb = rc_elems_per_block();
-    std::vector<RcBatch> batches;
-    {
+    // calls fn(batch) for every launch-sized group of tensors, in order
+    auto for_each_batch = [&](auto&& fn) -> hipError_t {
         RcBatch b;
         b.n_tensors = 0; b.total_blocks = 0;
         int64_t goff = 0, blocks = 0;
@@ -762,7 +796,8 @@ int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
             const int64_t nb = (numel[i] + epb - 1) / epb;
             if (b.n_tensors == kMaxTensorsPerLaunch || blocks + nb > 0x3fffffff) {
                 b.total_blocks = int32_t(blocks);
-                batches.push_back(b);
+                const hipError_t e = fn(b);
+                if (e != hipSuccess) return e;
                 b.n_tensors = 0; blocks = 0;
             }
             RcTensor& t = b.t[b.n_tensors++];
@@ -771,20 +806,49 @@ int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
             blocks += nb;
             goff += numel[i];
         }
-        if (b.n_tensors > 0) { b.total_blocks = int32_t(blocks); batches.push_back(b); }
-    }
-
-    ProfScope prof(ctx, stream, TF_KERNEL_RECONCILE);
-    RcState* st = ctx->rc_state;
-    hipError_t e = launch_rc_begin(stream, st);
-    for (RcBatch& b : batches) if (e == hipSuccess) e = launch_rc_count(stream, b, st);
+        if (b.n_tensors > 0) { b.total_blocks = int32_t(blocks); return fn(b); }
+        return hipSuccess;
+    };
+    hipError_t e = launch_rc_begin(stream, st);               // a kernel clears the state: nothing survives from the call before
+    if (e == hipSuccess) e = for_each_batch([&](RcBatch& b) { return launch_rc_count(stream, b, st); });
     if (e == hipSuccess) e = launch_rc_decide(stream, st, uint64_t(n_freeze), stats);
     const int shifts[3] = {21, 10, 0}, widths[3] = {11, 11, 10};
     for (int pass = 0; pass < 3; ++pass) {
-        for (RcBatch& b : batches) if (e == hipSuccess) e = launch_rc_hist(stream, b, st, keys, shifts[pass], widths[pass]);
+        if (e == hipSuccess) e = for_each_batch([&](RcBatch& b) { return launch_rc_hist(stream, b, st, keys, shifts[pass], widths[pass]); });
         if (e == hipSuccess) e = launch_rc_pick(stream, st, widths[pass], pass == 2, stats);
     }
-    for (RcBatch& b : batches) if (e == hipSuccess) e = launch_rc_apply(stream, b, st, keys);
+    if (e == hipSuccess) e = for_each_batch([&](RcBatch& b) { return launch_rc_apply(stream, b, st, keys); });
+    return e;
+}
+
+int tf_reconcile_mask(tf_ctx* ctx, void* hip_stream,
+                      int32_t n_tensors, const int64_t* numel,
+                      uint32_t* const* elem_bits,
+                      int64_t n_freeze, uint64_t seed,
+                      int64_t* stats) {
+    const int rc = validate_reconcile(n_tensors, numel, elem_bits, n_freeze, stats);
+    if (rc != TF_OK) return rc;
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    if (!use_device(ctx)) return TF_ERR_HIP;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    ProfScope prof(ctx, stream, TF_KERNEL_RECONCILE);
+    const hipError_t e = reconcile_passes(stream, n_tensors, numel, elem_bits, n_freeze, seed, stats, ctx->rc_state);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    return TF_OK;
+}
+
+int tf_reconcile_mask_static(tf_ctx* ctx, void* hip_stream,
+                             int32_t n_tensors, const int64_t* numel,
+                             uint32_t* const* elem_bits,
+                             int64_t n_freeze, uint64_t seed,
+                             int64_t* stats) {
+    const int rc = validate_reconcile(n_tensors, numel, elem_bits, n_freeze, stats);     // sizes beyond 2^32 - 1 elements: TF_ERR_SHAPE
+    if (rc != TF_OK) return rc;
+    if (!ctx || !ctx->rc_state_static) return TF_ERR_INVALID_ARG;
+    if (!use_device(ctx)) return TF_ERR_HIP;
+    // no timing events here: creating one allocates
+    const hipError_t e = reconcile_passes(static_cast<hipStream_t>(hip_stream), n_tensors, numel, elem_bits, n_freeze,
+                                          seed, stats, ctx->rc_state_static);
     if (e != hipSuccess) return hip_fail(ctx, e);
     return TF_OK;
 }
