@@ -6,12 +6,17 @@ A "step" is one pass of the whole hot path over one synthetic microbatch:
   tf_stage_backward (dX for every layer, dW for unfrozen layers only)
   -> tf_masked_adamw fused with the stability EMAs and per-tensor score sums
   -> score sums to host -> tf_stability_scores -> tf_select_lowest.
-The workload is the LLaMA-1B-shaped stage (4 blocks, d=2048, GQA kv=512,
-ffn=8192, 4x2048 tokens, bf16 with fp32 master weights and Adam states); the
-mask freezes the ceil(r*L) tensors with the lowest APF score after 5 seeded
-warm-up optimizer steps.  `value` is tokens/s at r = 0.5; the sweep over r is
-reported in "sweep".  Inputs are seeded and synthetic (workloads.py) and are
-resident in HBM before the timed region starts.
+The default run times the largest single-GPU configuration, the LLaMA-8B-shaped
+stage (8 blocks, d=4096, GQA kv=1024, ffn=14336, 4096 tokens, bf16 with fp32
+master weights and Adam states; the mask freezes the first ceil(r*L) tensors of
+a seeded permutation): `value` is its tokens/s at r = 0.5, "sweep" its sweep
+over r.  On the same tensors it then times the elementwise pass alone with
+per-element Bernoulli masks ("elementwise_8b") and eight microbatches of 1024
+tokens with fp32 accumulation ("microbatches_8b"), and finally the
+LLaMA-1B-shaped stage with its five-point sweep ("llama1b_stage": lowest APF
+scores after 5 seeded warm-up steps).  --workload N runs one of them alone.
+Inputs are seeded and synthetic (workloads.py) and are resident in HBM before
+the timed region starts.
 
 One JSON line is printed on stdout; progress goes to stderr.
 """
@@ -47,8 +52,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=2, choices=[2, 3, 4, 5, 6, 7, 8],
-                    help="config id: 2 = LLaMA-1B-shaped stage (the benchmark line); 3 = LLaMA-8B stage; "
+    ap.add_argument("--workload", type=int, default=0, choices=[0, 2, 3, 4, 5, 6, 7, 8],
+                    help="0 = the benchmark line (LLaMA-8B stage, then the elementwise pass and the 8 microbatches on "
+                         "its tensors, then the LLaMA-1B stage); config id: 2 = LLaMA-1B-shaped stage; 3 = LLaMA-8B stage; "
                          "4 = elementwise pass only, Bernoulli element masks; 5 = 8 microbatches with fp32 dW accumulation; "
                          "6 = selection steps on the 8B stage's tensors (AutoFreeze norms, Alg. 2 budget reconciliation); "
                          "7 = the benchmark stage with sub-tensor freezing (256-row blocks drawn under the parameter budget r P); "
@@ -133,7 +139,7 @@ def cpu_baseline(cfg, wl, r):
     """Time the fp64 oracle on a bounded sample of the same workload: block 0's
     seven layers, the first Ts tokens, backward at ratio r + AdamW/EMA step."""
     import oracle
-    Ts = 2048
+    Ts = 2048 if cfg.d <= 2048 else 768          # about 10-20 s of host work either way
     sub = wl.scaled(cfg, blocks=1)
     sh = sub.shapes
     mask = wl.permutation_mask(sub, r)
@@ -166,65 +172,31 @@ def cpu_baseline(cfg, wl, r):
     }
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU's stage; --gpus N with N > 1 is not supported "
-              "(no collectives or sharding are part of this library).", file=sys.stderr)
-        sys.exit(2)
-    import torch
-    import workloads as wl
-    import paper_2602_05754_amd as tf
+TRAFFIC_NOTE = ("HBM bytes per launch from separate rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this workload, "
+                "calibrated on a 1 GiB copy and recorded in profiles/hbm_traffic.txt; not counted in this run")
 
-    if not torch.cuda.is_available():
-        print("bench.py needs a GPU", file=sys.stderr)
-        sys.exit(2)
-    if not os.path.exists(tf.library_path()):
-        raise RuntimeError("libtf.so has not been built (python -c 'import __graft_entry__ as g; g.build()')")
-    torch.cuda.set_device(0)
-    if args.calibrate_copy:
-        n = 1 << 30
-        a = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
-        b = torch.empty_like(a)
+
+def warmup_scores(cfg, st, ctx, wl, tf, torch):
+    """cfg 2's mask source: 5 seeded optimizer steps with nothing frozen, then the APF scores."""
+    t0 = time.time()
+    for s in range(1, 6):
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            grads = list(ex.map(lambda l: wl.f32_to_bf16_bits(wl.gen_grad(cfg, l, s)).view(np.int16), range(st.L)))
+        gd = [torch.from_numpy(g).cuda().view(torch.bfloat16) for g in grads]
+        st.adamw(ctx, gd, None)
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(5):
-            b.copy_(a)
-        torch.cuda.synchronize()
-        dt = (time.perf_counter() - t0) / 5
-        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n,
-                          "GBps": 2 * n / dt / 1e9}), flush=True)
-        return
-    cfg = wl.CONFIGS[{6: 3, 7: 2, 8: 2}.get(args.workload, args.workload)]
-    ctx = tf.Context(0)
-    if args.workload == 4:
-        return bench_elementwise(args, cfg, ctx, wl, tf, torch)
-    if args.workload == 5:
-        return bench_microbatches(args, cfg, ctx, wl, tf, torch)
-    if args.workload == 6:
-        return bench_selection(args, cfg, ctx, wl, tf, torch)
-    if args.workload == 7:
-        return bench_row_blocks(args, cfg, ctx, wl, tf, torch)
-    if args.workload == 8:
-        return bench_shared_inputs(args, cfg, ctx, wl, tf, torch)
-    st = Stage(cfg, wl, tf, torch)
+        del gd, grads
+    scores = tf.tf_stability_scores(st.sums.cpu().numpy())
+    log(f"warm-up optimizer steps done in {time.time() - t0:.1f}s; score range {scores.min():.4f}..{scores.max():.4f}")
+    return scores
+
+
+def stage_report(args, cfg, st, ctx, wl, tf, torch, headline_r, sweep_rs, zero_operands):
+    """Times the whole step of one stage configuration at headline_r and over sweep_rs; returns
+    (head, sweep, rooflines) with the per-kernel event times of the launches of the timed steps."""
     L, T, P = st.L, st.T, cfg.n_params
-
-    # ---- mask selection ----
-    # cfg 2: 5 seeded warm-up optimizer steps with nothing frozen, then the lowest APF scores.
-    # cfg 3: the first ceil(r L) entries of a seeded permutation (as that configuration is stated).
-    scores = None
-    if cfg.cfg_id == 2:
-        t0 = time.time()
-        for s in range(1, 6):
-            with ThreadPoolExecutor(max_workers=8) as ex:
-                grads = list(ex.map(lambda l: wl.f32_to_bf16_bits(wl.gen_grad(cfg, l, s)).view(np.int16), range(L)))
-            gd = [torch.from_numpy(g).cuda().view(torch.bfloat16) for g in grads]
-            st.adamw(ctx, gd, None)
-            torch.cuda.synchronize()
-            del gd, grads
-        scores = tf.tf_stability_scores(st.sums.cpu().numpy())
-        log(f"warm-up optimizer steps done in {time.time() - t0:.1f}s; score range {scores.min():.4f}..{scores.max():.4f}")
+    # cfg 2: lowest APF scores after the warm-up steps; cfg 3: first ceil(r L) of a seeded permutation
+    scores = warmup_scores(cfg, st, ctx, wl, tf, torch) if cfg.cfg_id == 2 else None
 
     def run(r, steps, warmup):
         n = tf.tf_num_frozen(r, L)
@@ -263,52 +235,54 @@ def main():
             out["adamw_ms"] = a_ms
             out["adamw_gbps"] = 44.0 * unfrozen / (a_ms / 1e3) / 1e9
             out["adamw_pct_hbm_peak"] = 100.0 * out["adamw_gbps"] / PEAK_HBM_GBPS
-        return out, mask
+        return out
 
-    head, head_mask = run(HEADLINE_R, args.steps, args.warmup)
-    log(f"r={HEADLINE_R}: {head['ms_per_step']:.3f} ms/step, {head['tokens_per_s']:.0f} tok/s, "
+    head = run(headline_r, args.steps, args.warmup)
+    head["mask"] = ("ceil(r*L) lowest APF scores after 5 seeded warm-up steps" if scores is not None
+                    else "first ceil(r*L) entries of a seeded permutation")
+    log(f"cfg{cfg.cfg_id} r={headline_r}: {head['ms_per_step']:.3f} ms/step, {head['tokens_per_s']:.0f} tok/s, "
         f"backward {head['backward_tflops']:.0f} TFLOP/s")
     sweep = []
-    if not args.no_sweep:
-        for r in wl.R_SWEEP[cfg.cfg_id] + [1.0]:
-            s, _ = run(r, args.steps, 2) if r != HEADLINE_R else (head, None)
-            sweep.append(s)
-            log(f"sweep r={r}: phi={s['phi']:.3f} {s['ms_per_step']:.3f} ms/step, backward {s['backward_ms']:.3f} ms")
-        t_by_r = {s["r"]: s for s in sweep}
-        if 0.0 in t_by_r and 1.0 in t_by_r:
-            b0, b1 = t_by_r[0.0]["backward_ms"], t_by_r[1.0]["backward_ms"]
-            for s in sweep:
-                if 0.0 < s["r"] < 1.0 and s["phi"] > 0:
-                    # time saved relative to what the skipped dW FLOP fraction would ideally save
-                    s["eta_backward"] = (b0 - s["backward_ms"]) / (s["phi"] * (b0 - b1))
-                    d0 = t_by_r[0.0]["kernels"].get("dw_mfma", {}).get("avg_ms")
-                    dr = s["kernels"].get("dw_mfma", {}).get("avg_ms")
-                    if d0 and dr:   # the same slope on the dW kernel alone (dX does not depend on r)
-                        s["eta_dw_kernel"] = (d0 - dr) / (s["phi"] * d0)
+    for r in sweep_rs:
+        s = run(r, args.steps, 2) if r != headline_r else head
+        sweep.append(s)
+        log(f"cfg{cfg.cfg_id} sweep r={r}: phi={s['phi']:.3f} {s['ms_per_step']:.3f} ms/step, backward {s['backward_ms']:.3f} ms")
+    t_by_r = {s["r"]: s for s in sweep}
+    if 0.0 in t_by_r and 1.0 in t_by_r:
+        b0, b1 = t_by_r[0.0]["backward_ms"], t_by_r[1.0]["backward_ms"]
+        for s in sweep:
+            if 0.0 < s["r"] < 1.0 and s["phi"] > 0:
+                # time saved relative to what the skipped dW FLOP fraction would ideally save
+                s["eta_backward"] = (b0 - s["backward_ms"]) / (s["phi"] * (b0 - b1))
+                d0 = t_by_r[0.0]["kernels"].get("dw_mfma", {}).get("avg_ms")
+                dr = s["kernels"].get("dw_mfma", {}).get("avg_ms")
+                if d0 and dr:   # the same slope on the dW kernel alone (dX does not depend on r)
+                    s["eta_dw_kernel"] = (d0 - dr) / (s["phi"] * d0)
 
     # ---- roofline of the dominant kernel: the grouped input-gradient GEMM ----
+    roof = {}
     dx = head["kernels"].get("dx_mfma")
-    roofline = None
     if dx:
         fl = 2.0 * T * P / dx["launches_per_step"]
         ach = fl / (dx["avg_ms"] / 1e3) / 1e12
-        roofline = {"kernel": "gemm_mfma_kernel<NT> (dX = dY W^T, all layers, one grouped launch)",
-                    "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": read_traffic("dx_mfma", cfg.cfg_id),
-                    "avg_launch_ms": dx["avg_ms"], "flop_per_launch": fl}
-    if roofline and not args.no_sweep:
+        roof["roofline"] = {"kernel": "gemm_mfma_kernel<NT> (dX = dY W^T, all layers, one grouped launch)",
+                            "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                            "frac": ach / PEAK_BF16_TFLOPS, "traffic": read_traffic("dx_mfma", cfg.cfg_id),
+                            "traffic_source": TRAFFIC_NOTE, "avg_launch_ms": dx["avg_ms"], "flop_per_launch": fl}
+    if dx and zero_operands:
         # The same launch on all-zero operands.  Data decides how far the chip can clock under its
         # power limit: with nothing toggling in the matrix cores the clock stays near its maximum
         # and the figure shows what the instruction stream itself delivers.  Context for `frac`,
         # which is measured on the seeded inputs above.
-        zW = [torch.zeros_like(w) for w in st.W]
-        zdY = [torch.zeros_like(g) for g in st.dY]
+        zW = [torch.zeros_like(st.W[l]) for l in range(L)]
+        zdY = [torch.zeros_like(st.dY[l]) for l in range(L)]
         all_frozen = np.ones(L, dtype=np.uint8)
 
         def dx_only():
             tf.tf_stage_backward(ctx, st.shapes, st.T, tf.TF_BF16, zW, st.X, zdY, all_frozen, st.dX, st.dW, tf.TF_BF16)
 
-        for _ in range(40):
+        n_warm = max(4, int(120.0 / dx["avg_ms"]))              # the clock settles over the first 100 ms of load
+        for _ in range(n_warm):
             dx_only()
         torch.cuda.synchronize()
         ctx.profile_enable(True)
@@ -321,61 +295,129 @@ def main():
         del zW, zdY
         if ms0:
             ach0 = 2.0 * T * P / (float(np.sum(ms0)) / 20 / 1e3) / 1e12
-            roofline["achieved_zero_operands"] = ach0
-            roofline["frac_zero_operands"] = ach0 / PEAK_BF16_TFLOPS
-            log(f"dX launch on all-zero operands: {ach0:.0f} TFLOP/s")
-    extra = {}
+            roof["roofline"]["achieved_zero_operands"] = ach0
+            roof["roofline"]["frac_zero_operands"] = ach0 / PEAK_BF16_TFLOPS
+            log(f"cfg{cfg.cfg_id} dX launch on all-zero operands: {ach0:.0f} TFLOP/s")
     dw = head["kernels"].get("dw_mfma")
     if dw:
         fl = 2.0 * T * P * (1.0 - head["phi"]) / dw["launches_per_step"]
         ach = fl / (dw["avg_ms"] / 1e3) / 1e12
-        extra["roofline_dw"] = {"kernel": "gemm_mfma_kernel<TN> (dW = X^T dY, unfrozen layers only)", "bound": "mfma",
-                                "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                                "frac": ach / PEAK_BF16_TFLOPS, "traffic": read_traffic("dw_mfma", cfg.cfg_id),
-                                "avg_launch_ms": dw["avg_ms"]}
+        roof["roofline_dw"] = {"kernel": "gemm_mfma_kernel<TN> (dW = X^T dY, unfrozen layers only)", "bound": "mfma",
+                               "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                               "frac": ach / PEAK_BF16_TFLOPS, "traffic": read_traffic("dw_mfma", cfg.cfg_id),
+                               "traffic_source": TRAFFIC_NOTE, "avg_launch_ms": dw["avg_ms"]}
     if "adamw_gbps" in head:
-        extra["roofline_adamw"] = {"kernel": "ew_kernel (masked AdamW + APF EMAs + score sums)", "bound": "hbm",
-                                   "achieved": head["adamw_gbps"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                                   "frac": head["adamw_gbps"] / PEAK_HBM_GBPS,
-                                   "traffic": read_traffic("adamw", cfg.cfg_id), "avg_launch_ms": head["adamw_ms"]}
+        roof["roofline_adamw"] = {"kernel": "ew_kernel (masked AdamW + APF EMAs + score sums)", "bound": "hbm",
+                                  "achieved": head["adamw_gbps"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                  "frac": head["adamw_gbps"] / PEAK_HBM_GBPS,
+                                  "traffic": read_traffic("adamw", cfg.cfg_id), "traffic_source": TRAFFIC_NOTE,
+                                  "avg_launch_ms": head["adamw_ms"]}
+    return head, sweep, roof
 
-    cpu = None
-    if not args.no_cpu_baseline:
-        log("timing the fp64 oracle on a bounded sample (host cores)...")
-        cpu = cpu_baseline(cfg, wl, HEADLINE_R)
-        log(f"oracle: {cpu['value']:.2f} tokens/s on {cpu['cores']} threads")
 
+def lp_example(sweep, tf):
+    """What the measured times mean for the method (context, not a metric): a 4-stage, 8-microbatch
+    pipeline of such stages, every backward action between the measured r = 1 and r = 0 times,
+    forward = the r = 1 backward (same GEMM FLOPs as dX), through the freeze-ratio linear program."""
+    t_by_r = {x["r"]: x for x in sweep}
+    if 0.0 not in t_by_r or 1.0 not in t_by_r:
+        return None
+    S_, M_ = 4, 8
+    hi, lo = t_by_r[0.0]["backward_ms"], t_by_r[1.0]["backward_ms"]
+    w_max = np.r_[np.full(S_ * M_, lo), np.full(S_ * M_, hi)]
+    w_min = np.r_[np.full(S_ * M_, lo), np.full(S_ * M_, lo)]
+    ex = {}
+    for name, sched in (("gpipe", tf.TF_SCHEDULE_GPIPE), ("1f1b", tf.TF_SCHEDULE_1F1B)):
+        sol = tf.tf_freeze_ratio_lp(S_, M_, sched, w_min, w_max, 0.8, 1e-4)
+        ex[name] = {"batch_ms_no_freezing": sol["P_d_max"], "batch_ms_at_r_star": sol["P_d"],
+                    "mean_r_star": float(np.mean(sol["r"][S_ * M_:])),
+                    "throughput_gain_pct": 100.0 * (sol["P_d_max"] / sol["P_d"] - 1.0)}
+    return {"stages": S_, "microbatches": M_, "r_max": 0.8, "lambda": 1e-4, "backward_ms_r0": hi, "backward_ms_r1": lo, **ex}
+
+
+def workload_name(cfg, L, P):
+    return (f"cfg{cfg.cfg_id} {cfg.name}: {cfg.blocks} blocks, d={cfg.d}, kv={cfg.kv}, ffn={cfg.ffn}, "
+            f"T={cfg.T} tokens, L={L} tensors, P={P} params")
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU's stage; --gpus N with N > 1 is not supported "
+              "(no collectives or sharding are part of this library).", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import workloads as wl
+    import paper_2602_05754_amd as tf
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    if not os.path.exists(tf.library_path()):
+        raise RuntimeError("libtf.so has not been built (python -c 'import __graft_entry__ as g; g.build()')")
+    torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        n = 1 << 30
+        a = torch.full((n,), 7, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / 5
+        print(json.dumps({"calibrate_copy_bytes_read": n, "calibrate_copy_bytes_written": n,
+                          "GBps": 2 * n / dt / 1e9}), flush=True)
+        return
+    ctx = tf.Context(0)
+    if args.workload in (4, 5, 6, 7, 8):
+        cfg = wl.CONFIGS[{6: 3, 7: 2, 8: 2}.get(args.workload, args.workload)]
+        fn = {4: bench_elementwise, 5: bench_microbatches, 6: bench_selection, 7: bench_row_blocks, 8: bench_shared_inputs}
+        out = fn[args.workload](args, cfg, ctx, wl, tf, torch)
+        ctx.close()
+        print(json.dumps(out), flush=True)
+        return
+
+    # ---- the headline stage: cfg 3 by default (the largest configuration one GPU holds) ----
+    cfg = wl.CONFIGS[2 if args.workload == 2 else 3]
+    st = Stage(cfg, wl, tf, torch)
+    L, P = st.L, cfg.n_params
+    sweep_rs = [] if args.no_sweep else wl.R_SWEEP[cfg.cfg_id] + [1.0]
+    head, sweep, roof = stage_report(args, cfg, st, ctx, wl, tf, torch, HEADLINE_R, sweep_rs, zero_operands=not args.no_sweep)
     line = {
         "metric": f"stage-backward tokens/s (freeze-aware backward + masked AdamW + APF EMAs), r={HEADLINE_R}",
         "value": head["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"cfg{cfg.cfg_id} {cfg.name}: {cfg.blocks} blocks, d={cfg.d}, kv={cfg.kv}, ffn={cfg.ffn}, "
-                               f"T={cfg.T} tokens, L={L} tensors, P={P} params",
-                   "r": HEADLINE_R, "n_frozen": head["n_frozen"], "phi": head["phi"],
-                   "mask": "ceil(r*L) lowest APF scores after 5 seeded warm-up steps" if scores is not None
-                           else "first ceil(r*L) entries of a seeded permutation"},
-        "tflops": head["tflops"], "roofline": roofline, "cpu_baseline": cpu, "sweep": sweep,
+        "config": {"workload": workload_name(cfg, L, P), "r": HEADLINE_R, "n_frozen": head["n_frozen"],
+                   "phi": head["phi"], "mask": head["mask"]},
+        "tflops": head["tflops"], "roofline": roof.get("roofline"), "cpu_baseline": None, "sweep": sweep,
         "paper_context": PAPER_CONTEXT,
     }
-    line.update(extra)
-    t_by_r = {x["r"]: x for x in sweep}
-    if 0.0 in t_by_r and 1.0 in t_by_r:
-        # What the measured times mean for the method (context, not a metric): a 4-stage, 8-microbatch
-        # pipeline of such stages, every backward action between the measured r = 1 and r = 0 times,
-        # forward = the r = 1 backward (same GEMM FLOPs as dX), through the freeze-ratio linear program.
-        S_, M_ = 4, 8
-        hi, lo = t_by_r[0.0]["backward_ms"], t_by_r[1.0]["backward_ms"]
-        w_max = np.r_[np.full(S_ * M_, lo), np.full(S_ * M_, hi)]
-        w_min = np.r_[np.full(S_ * M_, lo), np.full(S_ * M_, lo)]
-        ex = {}
-        for name, sched in (("gpipe", tf.TF_SCHEDULE_GPIPE), ("1f1b", tf.TF_SCHEDULE_1F1B)):
-            sol = tf.tf_freeze_ratio_lp(S_, M_, sched, w_min, w_max, 0.8, 1e-4)
-            ex[name] = {"batch_ms_no_freezing": sol["P_d_max"], "batch_ms_at_r_star": sol["P_d"],
-                        "mean_r_star": float(np.mean(sol["r"][S_ * M_:])),
-                        "throughput_gain_pct": 100.0 * (sol["P_d_max"] / sol["P_d"] - 1.0)}
-        line["schedule_lp_example"] = {"stages": S_, "microbatches": M_, "r_max": 0.8, "lambda": 1e-4,
-                                       "backward_ms_r0": hi, "backward_ms_r1": lo, **ex}
+    line.update({k: v for k, v in roof.items() if k != "roofline"})
+    ex = lp_example(sweep, tf)
+    if ex:
+        line["schedule_lp_example"] = ex
+    if args.workload == 0:
+        # the other configurations, each with its own workload name and rooflines
+        line["elementwise_8b"] = bench_elementwise(args, wl.CONFIGS[4], ctx, wl, tf, torch, st=st)
+        line["microbatches_8b"] = bench_microbatches(args, wl.CONFIGS[5], ctx, wl, tf, torch, st=st)
+        del st
+        gc.collect()
+        torch.cuda.empty_cache()
+        cfg2 = wl.CONFIGS[2]
+        st2 = Stage(cfg2, wl, tf, torch)
+        h2, sw2, roof2 = stage_report(args, cfg2, st2, ctx, wl, tf, torch, HEADLINE_R, wl.R_SWEEP[2] + [1.0], zero_operands=False)
+        line["llama1b_stage"] = {"workload": workload_name(cfg2, st2.L, cfg2.n_params), "r": HEADLINE_R, "mask": h2["mask"],
+                                 "ms_per_step": h2["ms_per_step"], "tokens_per_s": h2["tokens_per_s"], "sweep": sw2, **roof2}
+        ex2 = lp_example(sw2, tf)
+        if ex2:
+            line["llama1b_stage"]["schedule_lp_example"] = ex2
+        del st2
+    if not args.no_cpu_baseline:
+        log("timing the fp64 oracle on a bounded sample (host cores)...")
+        line["cpu_baseline"] = cpu_baseline(cfg, wl, HEADLINE_R)
+        log(f"oracle: {line['cpu_baseline']['value']:.2f} tokens/s on {line['cpu_baseline']['cores']} threads")
     ctx.close()
     print(json.dumps(line), flush=True)
 
@@ -399,24 +441,28 @@ def _timed(ctx, torch, fn, steps, warmup):
     return dt, prof
 
 
-def bench_elementwise(args, cfg, ctx, wl, tf, torch):
-    """cfg 4: masked AdamW + APF EMAs over the 8B stage's 1.74e9 parameters with per-element
+def bench_elementwise(args, cfg, ctx, wl, tf, torch, st=None):
+    """cfg 4: masked AdamW + APF EMAs over the 8B stage's 1.74e9 parameters, dense and with per-element
     Bernoulli(r) masks.  Timing-only inputs: same distributions as workloads.py but drawn on the
     device (a seeded torch generator), because 3.5e9 host draws would take minutes; parity of this
-    pass is covered by the tests at one block of the same tensors."""
+    pass is covered by the tests at one block of the same tensors.  With `st` (a Stage of the same
+    tensors) its master weights and states are used as they stand after the stage's steps."""
     sizes = [k * n for k, n in cfg.shapes]
     L, P = len(sizes), sum(sizes)
     g = torch.Generator(device="cuda").manual_seed(wl.SEED_BASE + 4)
     rn = lambda n, std, dt=torch.float32: (torch.randn(n, generator=g, device="cuda") * std).to(dt)
-    p = [rn(n, cfg.w_std) for n in sizes]
-    m = [rn(n, 3e-4) for n in sizes]; v = [rn(n, 1e-3).square_() for n in sizes]
-    E = [rn(n, 1e-5) for n in sizes]; A = [rn(n, 1e-4).abs_() for n in sizes]
-    grad = [rn(n, cfg.g_std, torch.bfloat16) for n in sizes]
-    low = [x.to(torch.bfloat16) for x in p]
+    if st is not None:
+        p, m, v, E, A, low = st.p, st.m, st.v, st.E, st.A, st.W
+    else:
+        p = [rn(n, cfg.w_std) for n in sizes]
+        m = [rn(n, 3e-4) for n in sizes]; v = [rn(n, 1e-3).square_() for n in sizes]
+        E = [rn(n, 1e-5) for n in sizes]; A = [rn(n, 1e-4).abs_() for n in sizes]
+        low = [x.to(torch.bfloat16) for x in p]
+    grad = tf.PtrTable([rn(n, cfg.g_std, torch.bfloat16) for n in sizes])
     hp = {k: float(np.float32(getattr(cfg, k))) for k in ("lr", "beta1", "beta2", "eps", "weight_decay")}
     log(f"cfg 4 buffers ready, {torch.cuda.memory_allocated() / 2**30:.1f} GiB")
     rows = []
-    for r in wl.R_SWEEP[4] + [0.0]:
+    for r in [0.0] + wl.R_SWEEP[4]:
         bits = None
         if r > 0:
             bits = [(torch.rand((n + 31) // 32 * 32, generator=g, device="cuda") < r).view(-1, 32).to(torch.int64)
@@ -430,7 +476,15 @@ def bench_elementwise(args, cfg, ctx, wl, tf, torch):
         rows.append({"r": r, "ms_kernels": kms, "ms_per_call": dt * 1e3, "algorithmic_GBps": alg / kms / 1e6,
                      "dense_equivalent_GBps": P * 44 / kms / 1e6, "pct_hbm_peak_dense_equivalent": P * 44 / kms / 1e6 / 80.0})
         log(f"cfg4 r={r}: {kms:.3f} ms, algorithmic {rows[-1]['algorithmic_GBps']:.0f} GB/s, dense-equivalent {rows[-1]['dense_equivalent_GBps']:.0f} GB/s")
-    print(json.dumps({"workload": "cfg4 llama8b-elementwise, 56 tensors, 1744830464 elements", "rows": rows}), flush=True)
+        del bits
+    dense = rows[0]
+    return {"workload": f"cfg4 {cfg.name}: {L} tensors, {P} elements, fp32 p/m/v/E/A + bf16 grad and copy, Bernoulli element masks",
+            "rows": rows,
+            "roofline": {"kernel": "ew_kernel (masked AdamW + APF EMAs), dense (r = 0)", "bound": "hbm",
+                         "achieved": dense["algorithmic_GBps"], "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                         "frac": dense["algorithmic_GBps"] / PEAK_HBM_GBPS, "traffic": read_traffic("adamw", 4),
+                         "traffic_source": TRAFFIC_NOTE, "avg_launch_ms": dense["ms_kernels"] / 2.0,
+                         "launches_per_call": 2, "bytes_per_call": P * 44.0}}
 
 
 def bench_row_blocks(args, cfg, ctx, wl, tf, torch):
@@ -471,7 +525,7 @@ def bench_row_blocks(args, cfg, ctx, wl, tf, torch):
     b0, b1 = rows[0]["backward_ms"], rows[-1]["backward_ms"]
     for x in rows[1:-1]:
         x["eta_backward"] = (b0 - x["backward_ms"]) / (x["phi"] * (b0 - b1))
-    print(json.dumps({"workload": f"cfg2 stage with 256-row-block freezing, L={L} tensors, P={P} params, T={T}", "rows": rows}), flush=True)
+    return {"workload": f"cfg2 stage with 256-row-block freezing, L={L} tensors, P={P} params, T={T}", "rows": rows}
 
 
 def bench_shared_inputs(args, cfg, ctx, wl, tf, torch):
@@ -498,7 +552,7 @@ def bench_shared_inputs(args, cfg, ctx, wl, tf, torch):
         ms = float(np.mean([t for k, t in prof if k == "dx_mfma"]))
         out[name] = {"dx_ms": ms, "dx_tflops": 2.0 * T * P / ms / 1e9}
         log(f"dX {name}: {ms:.3f} ms, {out[name]['dx_tflops']:.0f} TFLOP/s")
-    print(json.dumps({"workload": f"cfg2 stage, input gradients with and without shared-input groups, T={T}", **out}), flush=True)
+    return {"workload": f"cfg2 stage, input gradients with and without shared-input groups, T={T}", **out}
 
 
 def bench_selection(args, cfg, ctx, wl, tf, torch):
@@ -535,35 +589,58 @@ def bench_selection(args, cfg, ctx, wl, tf, torch):
                      "Gelements_per_s": P / kms / 1e6})
         log(f"reconcile r={r}: {kms:.3f} ms ({rows[-1]['Gelements_per_s']:.1f} G elements/s), case {int(st[1])}")
     out["reconcile"] = rows
-    print(json.dumps(out), flush=True)
+    return out
 
 
-def bench_microbatches(args, cfg, ctx, wl, tf, torch):
+def bench_microbatches(args, cfg, ctx, wl, tf, torch, st=None):
     """cfg 5: 8 sequential backward calls of 1 x 1024 tokens on the 8B stage, dW accumulated in fp32
     for unfrozen tensors only, a different freeze ratio per call.  One microbatch's seeded inputs are
-    generated and reused for all 8 calls (timing only; the accumulation parity test draws fresh ones)."""
-    st = Stage(cfg, wl, tf, torch)
-    L, T, P = st.L, st.T, cfg.n_params
-    acc = [torch.zeros((k, n), device="cuda") for k, n in st.shapes]
+    used for all 8 calls (timing only; the accumulation parity test draws fresh ones): its own draw,
+    or with `st` (a Stage of the same tensors at more tokens) the first 1024 tokens of that stage's."""
+    T = cfg.T
+    if st is None:
+        st = Stage(cfg, wl, tf, torch)
+        X, dY = st.X, st.dY
+    else:
+        X = tf.PtrTable([st.X[l][:T] for l in range(st.L)])
+        dY = tf.PtrTable([st.dY[l][:T] for l in range(st.L)])
+    L, P = st.L, cfg.n_params
+    dX = tf.PtrTable([st.dX[l][:T] for l in range(L)])
+    acc = tf.PtrTable([torch.zeros((k, n), device="cuda") for k, n in st.shapes])
     ratios = wl.microbatch_ratios(cfg)
     masks = [wl.permutation_mask(cfg, r, microbatch=i) for i, r in enumerate(ratios)]
     def one_step():
         for mk in masks:
-            tf.tf_stage_backward(ctx, st.shapes, T, tf.TF_BF16, st.W, st.X, st.dY, mk, st.dX, acc, tf.TF_F32, accumulate=True)
+            tf.tf_stage_backward(ctx, st.shapes, T, tf.TF_BF16, st.W, X, dY, mk, dX, acc, tf.TF_F32, accumulate=True)
     dt, prof = _timed(ctx, torch, one_step, args.steps, args.warmup)
     dx = [t for k, t in prof if k == "dx_mfma"]; dw = [t for k, t in prof if k == "dw_mfma"]
     per_call = []
     for i, (r, mk) in enumerate(zip(ratios, masks)):
         phi = wl.frozen_param_fraction(cfg, mk)
         tdx = float(np.mean(dx[i::len(masks)])); tdw = float(np.mean(dw[i::len(masks)]))
+        # minimum traffic of the accumulating dW launch: X and dY read once, the fp32 gradient read and written
         unfrozen_bytes = (1 - phi) * P * 8 + 2 * T * sum((k + n) * (0 if mk[l] else 1) for l, (k, n) in enumerate(st.shapes))
+        dw_flop = 2.0 * T * P * (1 - phi)
+        t_roof_ms = max(dw_flop / (PEAK_BF16_TFLOPS * 1e12), unfrozen_bytes / (PEAK_HBM_GBPS * 1e9)) * 1e3
         per_call.append({"r": r, "n_frozen": int(mk.sum()), "phi": phi, "dx_ms": tdx, "dw_ms": tdw,
-                         "dx_tflops": 2.0 * T * P / tdx / 1e9, "dw_tflops": 2.0 * T * P * (1 - phi) / tdw / 1e9,
-                         "dw_GBps_min_traffic": unfrozen_bytes / tdw / 1e6})
+                         "dx_tflops": 2.0 * T * P / tdx / 1e9, "dw_tflops": dw_flop / tdw / 1e9,
+                         "dw_GBps_min_traffic": unfrozen_bytes / tdw / 1e6, "dw_frac_of_its_roof": t_roof_ms / tdw})
         log(f"cfg5 call {i}: r={r} phi={phi:.3f} dX {tdx:.3f} ms ({per_call[-1]['dx_tflops']:.0f} TFLOP/s), "
-            f"dW {tdw:.3f} ms ({per_call[-1]['dw_tflops']:.0f} TFLOP/s, {per_call[-1]['dw_GBps_min_traffic']:.0f} GB/s of its minimum traffic)")
-    print(json.dumps({"workload": "cfg5 llama8b-1f1b-8mb: 8 calls of T=1024, fp32 dW accumulation", "ms_per_8_calls": dt * 1e3,
-                      "tokens_per_s": 8 * T / dt, "calls": per_call}), flush=True)
+            f"dW {tdw:.3f} ms ({per_call[-1]['dw_tflops']:.0f} TFLOP/s, {per_call[-1]['dw_GBps_min_traffic']:.0f} GB/s of its minimum traffic, "
+            f"{100 * per_call[-1]['dw_frac_of_its_roof']:.0f} % of max(MFMA, HBM) roof)")
+    tot_bytes = sum(c["dw_GBps_min_traffic"] * c["dw_ms"] * 1e6 for c in per_call)
+    tot_ms = sum(c["dw_ms"] for c in per_call)
+    return {"workload": f"cfg5 {cfg.name}: 8 calls of T={T}, fp32 dW accumulation, {L} tensors, P={P} params",
+            "ms_per_8_calls": dt * 1e3, "tokens_per_s": 8 * T / dt, "calls": per_call,
+            "roofline_dw": {"kernel": "gemm_mfma_kernel<TN, fp32 read-modify-write> (dW += X^T dY, unfrozen layers only), mean over the 8 calls",
+                            "bound": "hbm", "achieved": tot_bytes / tot_ms / 1e6, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                            "frac": tot_bytes / tot_ms / 1e6 / PEAK_HBM_GBPS, "traffic": read_traffic("dw_mfma", 5),
+                            "traffic_source": TRAFFIC_NOTE, "avg_launch_ms": tot_ms / len(per_call),
+                            "frac_of_max_mfma_hbm_roof": float(np.mean([c["dw_frac_of_its_roof"] for c in per_call]))},
+            "roofline_dx": {"kernel": "gemm_mfma_kernel<NT> at T=1024", "bound": "mfma",
+                            "achieved": float(np.mean([c["dx_tflops"] for c in per_call])), "peak": PEAK_BF16_TFLOPS,
+                            "unit": "TFLOP/s", "frac": float(np.mean([c["dx_tflops"] for c in per_call])) / PEAK_BF16_TFLOPS,
+                            "avg_launch_ms": float(np.mean([c["dx_ms"] for c in per_call]))}}
 
 
 def read_traffic(kernel: str, cfg_id: int):
