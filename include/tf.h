@@ -71,9 +71,10 @@ typedef enum {
 /* Create / destroy a context bound to HIP device `device_id`.  tf_create makes
  * that device current for the calling thread and queries its properties; it
  * fails with TF_ERR_NO_DEVICE when there is no such device.  The context owns
- * its host-side bookkeeping (timing events) and ONE device allocation, made here:
- * the 8.2 KB rank-search state of tf_reconcile_mask (TF_ERR_WORKSPACE if that
- * fails).  No call allocates device memory afterwards.  Every later call on the
+ * its host-side bookkeeping (timing events) and two small device allocations, made
+ * here: the 8.2 KB rank-search state of tf_reconcile_mask and 128 KB of partial
+ * score sums for tf_masked_adamw / tf_stability_update (TF_ERR_WORKSPACE if
+ * either fails).  No call allocates device memory afterwards.  Every later call on the
  * context makes device_id current for the calling thread before it launches. */
 int tf_create(tf_ctx** out, int device_id);
 int tf_destroy(tf_ctx* ctx);
@@ -174,7 +175,21 @@ int tf_stage_backward(tf_ctx* ctx, void* hip_stream,
  *                       contribute their unchanged values).  Entries of frozen
  *                       tensors are left as they were.  Requires ema/ema_abs.
  *   Arithmetic is fp32; sums are accumulated in fp64.
+ *   numel[i] <= 2^37 (TF_ERR_SHAPE beyond).
+ *
+ * Element masks are applied per mask word (32 elements, one 128-byte line of each
+ * fp32 buffer): a word of all ones is skipped altogether; in any other word the
+ * frozen elements are written back with the bits that were read, and their stored
+ * bf16 copy is read in order to be written back unchanged.
+ *
+ * tf_assume_lowp_is_rounded_master(ctx, 1): the caller promises that on entry to
+ * every later tf_masked_adamw on this context p_lowp[i][j] == bf16_rne(p_master[i][j])
+ * for all elements (true whenever the copies were produced by this function, or by
+ * rounding the master weights, and not changed since).  Frozen elements of a partly
+ * frozen word then get their copy from the unchanged p instead of a second read:
+ * the same bits under the promise, 2 bytes per element less traffic.  Off by default.
  */
+int tf_assume_lowp_is_rounded_master(tf_ctx* ctx, int on);
 int tf_masked_adamw(tf_ctx* ctx, void* hip_stream,
                     int32_t n_tensors, const int64_t* numel,
                     void* const* p_master, void* const* m, void* const* v,

@@ -20,7 +20,7 @@ EXPORTED_SYMBOLS = [
     "tf_create", "tf_destroy", "tf_strerror", "tf_last_hip_error", "tf_version",
     "tf_stage_backward", "tf_masked_adamw", "tf_stability_update",
     "tf_stability_scores", "tf_select_lowest", "tf_num_frozen",
-    "tf_profile_enable", "tf_profile_collect",
+    "tf_profile_enable", "tf_profile_collect", "tf_assume_lowp_is_rounded_master",
     "tf_autofreeze_norms", "tf_autofreeze_scores", "tf_autofreeze_select", "tf_reconcile_mask",
     "tf_reconcile_mask_static",
     "tf_stage_backward_blocks", "tf_stage_backward_shared", "tf_select_row_blocks", "tf_row_blocks_to_bits",
@@ -86,6 +86,8 @@ def load_library():
     lib.tf_num_frozen.argtypes = [f64, i32]
     lib.tf_profile_enable.restype = ctypes.c_int
     lib.tf_profile_enable.argtypes = [vp, ctypes.c_int]
+    lib.tf_assume_lowp_is_rounded_master.restype = ctypes.c_int
+    lib.tf_assume_lowp_is_rounded_master.argtypes = [vp, ctypes.c_int]
     lib.tf_profile_collect.restype = ctypes.c_int
     lib.tf_profile_collect.argtypes = [vp, i32, vp, vp, vp]
     lib.tf_autofreeze_norms.restype = ctypes.c_int
@@ -284,6 +286,12 @@ class Context:
         rc = load_library().tf_profile_enable(self._h, 1 if on else 0)
         if rc != 0:
             raise TfError(rc, "tf_profile_enable")
+
+    def assume_lowp_is_rounded_master(self, on: bool = True) -> None:
+        """tf_assume_lowp_is_rounded_master: see include/tf.h."""
+        rc = load_library().tf_assume_lowp_is_rounded_master(self._h, 1 if on else 0)
+        if rc != 0:
+            raise TfError(rc, "tf_assume_lowp_is_rounded_master")
 
     def profile_collect(self, capacity: int = 4096):
         """[(kernel kind name, milliseconds)] of the launches since the last collect."""

@@ -23,6 +23,8 @@ struct tf_ctx {
     std::vector<hipEvent_t> pool;       // events ready for reuse
     tf::RcState* rc_state;              // device memory of tf_reconcile_mask (radix-select state)
     tf::RcState* rc_state_static;       // this device's static scratch array (tf_reconcile_mask_static)
+    bool lowp_is_rounded_master;        // tf_assume_lowp_is_rounded_master
+    double* ew_partials;                // device memory of the score sums' first level (zero between launches)
 };
 
 // Device memory of tf_reconcile_mask_static: one array per GPU, part of the loaded code object,
@@ -202,7 +204,7 @@ int validate_elementwise_common(int32_t n_tensors, const int64_t* numel,
     if (score_sums && (reinterpret_cast<uintptr_t>(score_sums) & 7u)) return TF_ERR_ALIGN;
     for (int32_t i = 0; i < n_tensors; ++i) {
         if (numel[i] <= 0) return TF_ERR_SHAPE;
-        if (numel[i] > (int64_t(1) << 40)) return TF_ERR_SHAPE;
+        if (numel[i] > (int64_t(1) << 37)) return TF_ERR_SHAPE;      // 2^29 blocks of 256 elements per launch
         if (tensor_freeze_mask && tensor_freeze_mask[i] > 1) return TF_ERR_INVALID_ARG;
         if (tensor_freeze_mask && tensor_freeze_mask[i]) continue;
         if (ema) {
@@ -251,12 +253,17 @@ int tf_create(tf_ctx** out, int device_id) {
     ctx->profiling = false;
     ctx->rc_state = nullptr;
     ctx->rc_state_static = nullptr;
+    ctx->lowp_is_rounded_master = false;
+    ctx->ew_partials = nullptr;
     if (hipMalloc(reinterpret_cast<void**>(&ctx->rc_state), tf::rc_state_bytes()) != hipSuccess) {
         delete ctx;
         return TF_ERR_WORKSPACE;
     }
     void* st = nullptr;
-    if (static_scratch_address(device_id, &st) != hipSuccess) {      // device_id is current here
+    if (static_scratch_address(device_id, &st) != hipSuccess ||      // device_id is current here
+        hipMalloc(reinterpret_cast<void**>(&ctx->ew_partials), tf::ew_partials_bytes()) != hipSuccess ||
+        hipMemset(ctx->ew_partials, 0, tf::ew_partials_bytes()) != hipSuccess) {
+        if (ctx->ew_partials) (void)hipFree(ctx->ew_partials);
         (void)hipFree(ctx->rc_state);
         delete ctx;
         return TF_ERR_WORKSPACE;
@@ -271,7 +278,14 @@ int tf_destroy(tf_ctx* ctx) {
     for (tf_prof_rec& r : ctx->recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
     for (hipEvent_t e : ctx->pool) (void)hipEventDestroy(e);
     if (ctx->rc_state) (void)hipFree(ctx->rc_state);
+    if (ctx->ew_partials) (void)hipFree(ctx->ew_partials);
     delete ctx;
+    return TF_OK;
+}
+
+int tf_assume_lowp_is_rounded_master(tf_ctx* ctx, int on) {
+    if (!ctx || (on != 0 && on != 1)) return TF_ERR_INVALID_ARG;
+    ctx->lowp_is_rounded_master = on != 0;
     return TF_OK;
 }
 
@@ -539,6 +553,9 @@ int tf_masked_adamw(tf_ctx* ctx, void* hip_stream,
 
     const int64_t epb = ew_elems_per_block();
     EwBatch batch;
+    batch.lowp_is_rounded_master = ctx->lowp_is_rounded_master ? 1 : 0;
+    batch.pad_ = 0;
+    batch.partials = ctx->ew_partials;
     int n = 0;
     int64_t blocks = 0;
     auto flush = [&]() -> hipError_t {
@@ -568,8 +585,7 @@ int tf_masked_adamw(tf_ctx* ctx, void* hip_stream,
         t.numel = numel[i];
         t.rbc1 = float(1.0 / (1.0 - std::pow(double(beta1), double(step[i]))));
         t.rbc2 = float(1.0 / (1.0 - std::pow(double(beta2), double(step[i]))));
-        t.block_start = int32_t(blocks);
-        t.pad_ = 0;
+        batch.block_start[n] = int32_t(blocks);
         blocks += nb;
         ++n;
     }
@@ -610,6 +626,9 @@ int tf_stability_update(tf_ctx* ctx, void* hip_stream,
 
     const int64_t epb = ew_elems_per_block();
     EwBatch batch;
+    batch.lowp_is_rounded_master = 0;
+    batch.pad_ = 0;
+    batch.partials = ctx->ew_partials;
     int n = 0;
     int64_t blocks = 0;
     auto flush = [&]() -> hipError_t {
@@ -634,7 +653,7 @@ int tf_stability_update(tf_ctx* ctx, void* hip_stream,
         t.A = static_cast<float*>(ema_abs[i]);
         t.sums = score_sums ? score_sums + 2 * int64_t(i) : nullptr;
         t.numel = numel[i];
-        t.block_start = int32_t(blocks);
+        batch.block_start[n] = int32_t(blocks);
         blocks += nb;
         ++n;
     }

@@ -78,16 +78,29 @@ struct EwTensor {
     double* sums;           // optional: &score_sums[2*i]
     int64_t numel;
     float rbc1, rbc2;       // 1/(1-beta1^t), 1/(1-beta2^t)
-    int32_t block_start;    // first block of this tensor inside a launch
-    int32_t pad_;
 };
 
 constexpr int kMaxTensorsPerLaunch = 32;
 
+// Per-tensor score sums are gathered in two levels: a block adds its two partial sums to one of
+// kSumSlots slots of its tensor (one 64-byte line each, chosen by the block number), a second
+// small kernel adds up the slots.  With one pair of addresses per tensor, the atomics of the
+// 6.8 million one-wave blocks of the 8B stage would queue up behind each other (measured: 82 ms
+// instead of 13).  The slots live in device memory owned by the context and are zero between launches.
+constexpr int kSumSlots = 64;
+constexpr int kSumSlotDoubles = 8;      // 64 bytes: {sum |E|, sum A, unused...}
+inline size_t ew_partials_bytes() { return size_t(kMaxTensorsPerLaunch) * kSumSlots * kSumSlotDoubles * sizeof(double); }
+
 struct EwBatch {            // passed by value as the kernel argument (< 4 KB)
     EwTensor t[kMaxTensorsPerLaunch];
+    int32_t block_start[kMaxTensorsPerLaunch];      // first block of each tensor inside the launch
+    double* partials;       // the context's slots (device); needed only when some tensor wants sums
     int32_t n_tensors;
     int32_t total_blocks;
+    // the caller's promise that every bf16 copy equals the rounding of its master weights on entry:
+    // frozen elements of a partly frozen line then get their copy back from p instead of a re-read
+    int32_t lowp_is_rounded_master;
+    int32_t pad_;
 };
 
 struct AdamwParams {

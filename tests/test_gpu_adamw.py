@@ -276,3 +276,33 @@ def test_standalone_stability_update_with_more_tensors_than_one_launch_holds(ctx
             assert np.array_equal(Ed[i].cpu().numpy()[f], E0[i][f]) and np.array_equal(Ad[i].cpu().numpy()[f], A0[i][f]), i
         se, sa = oracle.score_sums(Eh[i], Ah[i])
         assert np.isclose(got[i, 0], se, rtol=1e-5, atol=1e-30) and np.isclose(got[i, 1], sa, rtol=1e-5, atol=1e-30), i
+
+
+def test_frozen_bf16_copies_under_the_rounded_master_promise(ctx):
+    """With tf_assume_lowp_is_rounded_master the stored bf16 copy of a frozen element in a partly
+    frozen mask word is not read again but rounded from the unchanged master weight: the same bits
+    whenever the copy was the rounding of p, as here (two steps, the second on copies the first wrote)."""
+    rs = np.random.default_rng(19)
+    sizes = [32 * 1000 + 17, 4096, 70_001]
+    states = [State(rs, n, zero_state=False, grad_dtype="bf16") for n in sizes]
+    elem = [(rs.random(n) < 0.6).astype(np.uint8) for n in sizes]
+    elem[1][:2048] = 1                                             # 64 wholly frozen words
+    bits = [torch.from_numpy(wl.pack_mask_bits(e).view(np.int32)).cuda() for e in elem]
+    ctx.assume_lowp_is_rounded_master(True)
+    try:
+        for rep in range(2):
+            grads = [s.grad(rs) for s in states]
+            before = [{k: raw_bytes(s.d[k]) for k in s.d} for s in states]
+            for i, s in enumerate(states):
+                oracle.masked_adamw(s.h["p"], s.h["m"], s.h["v"], grads[i].astype(np.float64), step=1 + rep,
+                                    p_lowp=s.h["low"], elem_frozen=elem[i], ema=s.h["E"], ema_abs=s.h["A"],
+                                    ema_decay=DECAY, **HP)
+            tf.tf_masked_adamw(ctx, sizes, [s.d["p"] for s in states], [s.d["m"] for s in states],
+                               [s.d["v"] for s in states], [dev(g, "bf16") for g in grads], tf.TF_BF16, [1 + rep] * 3,
+                               HP["lr"], HP["beta1"], HP["beta2"], HP["eps"], HP["weight_decay"],
+                               p_lowp=[s.d["low"] for s in states], elem_freeze_bits=bits,
+                               ema=[s.d["E"] for s in states], ema_abs=[s.d["A"] for s in states], ema_decay=DECAY)
+            torch.cuda.synchronize()
+            _check(states, elem, None, before, label=f"promise, step {rep}")
+    finally:
+        ctx.assume_lowp_is_rounded_master(False)
