@@ -16,6 +16,12 @@ acyclicity, start times against brute-force path enumeration, the GPipe and
 1F1B makespans for uniform action times in closed form, the LP against an
 exhaustive grid search on 2-stage / 2-microbatch schedules, the LP's batch
 time against the longest path at its own solution, monotonicity in r_max.
+Interleaved 1F1B and ZBV (Sec. 4.2 "Pipeline Schedules"; edge rule 4): rank
+orders written out by hand for small cases, the orders that the installed
+PyTorch's torch.distributed.pipelining generates for the same schedules (the
+training framework the paper names builds on it), every action exactly once
+on the rank that owns its stage, forward before backward, acyclicity, and the
+interleaved schedule's closed-form makespan for uniform action times.
 """
 from __future__ import annotations
 
@@ -25,7 +31,8 @@ from typing import Sequence
 
 import numpy as np
 
-GPIPE, ONE_F_ONE_B = 0, 1
+GPIPE, ONE_F_ONE_B, INTERLEAVED_1F1B, ZBV = 0, 1, 2, 3
+STAGES_PER_RANK = 2          # of the two schedules that place several stages on a rank
 
 
 def node_id(a: int, m: int, s: int, M: int, S: int) -> int:
@@ -33,7 +40,8 @@ def node_id(a: int, m: int, s: int, M: int, S: int) -> int:
 
 
 def rank_order(s: int, M: int, S: int, schedule: int):
-    """Order in which the rank of stage s runs its 2 M actions, as (a, m) pairs."""
+    """GPipe / 1F1B (one stage per rank): order in which the rank of stage s runs its 2 M
+    actions, as (a, m) pairs."""
     if schedule == GPIPE:
         return [(0, m) for m in range(M)] + [(1, m) for m in range(M)]
     warm = min(M, S - 1 - s)                       # forwards before the first backward
@@ -42,6 +50,104 @@ def rank_order(s: int, M: int, S: int, schedule: int):
         order += [(0, warm + i), (1, i)]
     order += [(1, m) for m in range(M - warm, M)]  # the remaining backwards
     return order
+
+
+def n_ranks(S: int, schedule: int) -> int:
+    if schedule in (GPIPE, ONE_F_ONE_B):
+        return S
+    if S % STAGES_PER_RANK:
+        raise ValueError("two stages per rank: the number of stages must be even")
+    return S // STAGES_PER_RANK
+
+
+def stage_rank(s: int, S: int, schedule: int) -> int:
+    """The rank that owns stage s."""
+    R = n_ranks(S, schedule)
+    if schedule == INTERLEAVED_1F1B:
+        return s % R                                # looped placement: stages r, r + R
+    if schedule == ZBV:
+        return s if s < R else 2 * R - 1 - s        # V-shaped placement: stages r, 2R - 1 - r
+    return s
+
+
+def _interleaved_order(r: int, M: int, R: int):
+    """Interleaved 1F1B on rank r of R with V = 2 model chunks per rank (stages r and r + R):
+    the rank works through V M forward and V M backward passes; pass k of either kind belongs
+    to chunk (k div g) mod V counted from the first chunk for forwards and from the last for
+    backwards, g = M / max(1, M div R) being the microbatches a chunk takes in a row; it runs
+    (V - 1) g + 2 (R - 1 - r) forwards ahead (at most all of them), then one forward / one
+    backward in turn, then the remaining backwards."""
+    V = STAGES_PER_RANK
+    rounds = max(1, M // R)
+    if M % rounds:
+        raise ValueError("the number of microbatches must be a multiple of the number of rounds")
+    g = M // rounds
+    total = V * M
+    warm = min((V - 1) * g + 2 * (R - 1 - r), total)
+    done = {}                                       # (a, stage) -> passes so far = next microbatch
+
+    def take(a, k):
+        chunk = (k // g) % V
+        if a == 1:
+            chunk = V - 1 - chunk
+        stage = chunk * R + r
+        m = done.get((a, stage), 0)
+        done[(a, stage)] = m + 1
+        return (a, m, stage)
+
+    order = [take(0, k) for k in range(warm)]
+    for k in range(total - warm):
+        order.append(take(0, warm + k))
+        order.append(take(1, k))
+    order += [take(1, k) for k in range(total - warm, total)]
+    return order
+
+
+def _zbv_order(r: int, M: int, R: int):
+    """Zero-bubble V schedule on rank r of R: chunk 0 is stage r, chunk 1 is stage 2R - 1 - r.
+    The schedule separates a backward into its input-gradient and its weight-gradient pass; the
+    DAG's backward node stands for both and sits where the input-gradient pass runs.  Phases:
+    2 (R - r) - 1 forwards of chunk 0; r times (forward chunk 1, forward chunk 0); R - r times
+    (forward chunk 1, backward chunk 1); the stable phase (forward chunk 0 while any is left,
+    backward chunk 0, forward chunk 1, backward chunk 1) until chunk 1 has caught up; then the
+    backwards that are left, r pairs (chunk 0, chunk 1) first and chunk 0 alone after.  The
+    schedule is laid out for max(M, 2R - 1) microbatches and those past M are dropped."""
+    n = max(M, 2 * R - 1)
+    cnt = {(0, 0): 0, (0, 1): 0, (1, 0): 0, (1, 1): 0}      # (a, chunk) -> passes so far
+    stage = (r, 2 * R - 1 - r)
+    order = []
+
+    def run(a, chunk):
+        m = cnt[(a, chunk)]
+        cnt[(a, chunk)] += 1
+        if m < M:
+            order.append((a, m, stage[chunk]))
+
+    for _ in range(2 * (R - r) - 1):
+        run(0, 0)
+    for _ in range(r):
+        run(0, 1); run(0, 0)
+    for _ in range(R - r):
+        run(0, 1); run(1, 1)
+    while cnt[(0, 1)] < cnt[(0, 0)] or cnt[(0, 0)] < n:
+        if cnt[(0, 0)] < n:
+            run(0, 0)
+        run(1, 0); run(0, 1); run(1, 1)
+    for _ in range(r):
+        run(1, 0); run(1, 1)
+    for _ in range(R - r):
+        run(1, 0)
+    return order
+
+
+def rank_orders(M: int, S: int, schedule: int):
+    """For every rank the list of (a, m, s) in the order the rank runs them (edge rule 4)."""
+    R = n_ranks(S, schedule)
+    if schedule == INTERLEAVED_1F1B:
+        return [_interleaved_order(r, M, R) for r in range(R)]
+    if schedule == ZBV:
+        return [_zbv_order(r, M, R) for r in range(R)]
+    return [[(a, m, s) for a, m in rank_order(s, M, S, schedule)] for s in range(S)]
 
 
 def pipeline_dag(S: int, M: int, schedule: int):
@@ -61,10 +167,9 @@ def pipeline_dag(S: int, M: int, schedule: int):
         for s in range(S - 1):
             E.add((nid(0, m, s), nid(0, m, s + 1)))
             E.add((nid(1, m, s + 1), nid(1, m, s)))
-    for s in range(S):                                             # rule 4: the rank's own order
-        order = rank_order(s, M, S, schedule)
-        for (a0, m0), (a1, m1) in zip(order, order[1:]):
-            E.add((nid(a0, m0, s), nid(a1, m1, s)))
+    for order in rank_orders(M, S, schedule):                      # rule 4: each rank's own order
+        for (a0, m0, s0), (a1, m1, s1) in zip(order, order[1:]):
+            E.add((nid(a0, m0, s0), nid(a1, m1, s1)))
     return sorted(E)
 
 

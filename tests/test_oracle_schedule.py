@@ -170,3 +170,139 @@ def test_progressive_ratio():
     assert sc.actual_freeze_ratio(0.6, 200, 100, 200) == pytest.approx(0.6)
     assert sc.actual_freeze_ratio(0.6, 5000, 100, 200) == 0.6
     assert sc.actual_freeze_ratio(0.6, 50, 100, 200) == 0.0
+
+
+# ---------------------------------------------------------------------------------------------
+# Interleaved 1F1B and ZBV (Sec. 4.2 "Pipeline Schedules"; edge rule 4): two stages per rank
+# ---------------------------------------------------------------------------------------------
+I, Z = sc.INTERLEAVED_1F1B, sc.ZBV
+
+
+def test_hand_drawn_rank_orders_of_the_two_stage_per_rank_schedules():
+    f = lambda m, s: (0, m, s)
+    b = lambda m, s: (1, m, s)
+    # 2 ranks, 4 stages, 2 microbatches.  Interleaved: rank r owns stages r and r + 2.  Rank 0 is three
+    # hops from the end of the pipeline and runs all four forwards ahead; rank 1 runs two, then alternates.
+    assert sc.rank_orders(2, 4, I) == [
+        [f(0, 0), f(1, 0), f(0, 2), f(1, 2), b(0, 2), b(1, 2), b(0, 0), b(1, 0)],
+        [f(0, 1), f(1, 1), f(0, 3), b(0, 3), f(1, 3), b(1, 3), b(0, 1), b(1, 1)]]
+    # ZBV: rank r owns stages r and 3 - r (the V).  Rank 0 holds the first and the last stage: its last-stage
+    # forwards are each followed at once by their backward; rank 1 holds the two middle stages.
+    assert sc.rank_orders(2, 4, Z) == [
+        [f(0, 0), f(1, 0), f(0, 3), b(0, 3), f(1, 3), b(1, 3), b(0, 0), b(1, 0)],
+        [f(0, 1), f(0, 2), f(1, 1), f(1, 2), b(0, 2), b(0, 1), b(1, 2), b(1, 1)]]
+    assert [sc.stage_rank(s, 8, I) for s in range(8)] == [0, 1, 2, 3, 0, 1, 2, 3]
+    assert [sc.stage_rank(s, 8, Z) for s in range(8)] == [0, 1, 2, 3, 3, 2, 1, 0]
+    # one rank: both schedules degenerate to "a microbatch's forwards, then ..." on a single device
+    assert sc.rank_orders(1, 2, Z) == [[f(0, 0), f(0, 1), b(0, 1), b(0, 0)]]
+    with pytest.raises(ValueError):
+        sc.rank_orders(2, 3, I)                       # an odd number of stages
+    with pytest.raises(ValueError):
+        sc.rank_orders(5, 4, I)                       # 5 microbatches on 2 ranks: not a whole number of rounds
+
+
+def _torch_rank_orders(kind, R, M):
+    """The same schedules as the installed PyTorch lays them out (torch.distributed.pipelining, on
+    which the training framework named in Sec. 4.2 builds): forward and input-gradient / full backward
+    passes in order, idle slots and weight-gradient passes left out."""
+    S = pytest.importorskip("torch.distributed.pipelining.schedules")
+    if kind == I:
+        o = object.__new__(S.ScheduleInterleaved1F1B)            # no process group: only the layout routine is used
+        o.pp_group_size, o.n_local_stages, o._n_microbatches = R, 2, M
+        o.number_of_rounds = max(1, M // R)
+        o.microbatches_per_round = M // o.number_of_rounds
+    else:
+        o = object.__new__(S.ScheduleZBVZeroBubble)
+        o.pp_group_size, o.n_local_stages, o._n_microbatches, o.num_stages = R, 2, M, 2 * R
+    out = []
+    for r in range(R):
+        seq = []
+        for act in o._calculate_single_rank_operations(r):
+            if act is None:
+                continue
+            kind_ = str(act.computation_type)
+            if kind_ == "F":
+                seq.append((0, act.microbatch_index, act.stage_index))
+            elif kind_ in ("B", "I"):
+                seq.append((1, act.microbatch_index, act.stage_index))
+        out.append(seq)
+    return out
+
+
+@pytest.mark.parametrize("sched", [I, Z])
+def test_rank_orders_equal_the_layout_of_the_installed_pipelining_library(sched):
+    checked = 0
+    for R in (1, 2, 3, 4, 5):
+        for M in (1, 2, 3, 4, 6, 8, 12, 16):
+            if sched == I and M % max(1, M // R):
+                continue
+            try:
+                ref = _torch_rank_orders(sched, R, M)
+            except (AttributeError, TypeError):
+                pytest.skip("this PyTorch lays its schedules out through another routine")
+            assert sc.rank_orders(M, 2 * R, sched) == ref, (R, M)
+            checked += 1
+    assert checked >= 30
+
+
+@pytest.mark.parametrize("S,M,sched", [(2, 1, I), (4, 2, I), (4, 4, I), (6, 3, I), (8, 8, I), (8, 4, I), (8, 3, I),
+                                       (2, 1, Z), (2, 3, Z), (4, 2, Z), (4, 5, Z), (6, 4, Z), (8, 8, Z), (8, 2, Z)])
+def test_every_action_once_on_its_own_rank_and_no_cycle(S, M, sched):
+    orders = sc.rank_orders(M, S, sched)
+    assert len(orders) == S // 2
+    for r, order in enumerate(orders):
+        stages = [s for s in range(S) if sc.stage_rank(s, S, sched) == r]
+        assert len(stages) == 2
+        assert sorted(order) == sorted((a, m, s) for a in (0, 1) for m in range(M) for s in stages)
+        for s in stages:
+            for m in range(M):
+                assert order.index((0, m, s)) < order.index((1, m, s))            # forward before its backward
+            for a in (0, 1):                                                       # microbatches in order within a stage
+                ms = [m for (a_, m, s_) in order if a_ == a and s_ == s]
+                assert ms == sorted(ms)
+        # a microbatch's forward reaches the rank's later stage after its earlier one; its backward the other way round
+        lo, hi = sorted(stages)
+        for m in range(M):
+            assert order.index((0, m, lo)) < order.index((0, m, hi))
+            assert order.index((1, m, hi)) < order.index((1, m, lo))
+    E = sc.pipeline_dag(S, M, sched)
+    n = 2 * M * S + 2
+    P = sc.start_times(n, E, np.ones(n))              # raises on a cycle
+    assert P[n - 1] > 0
+
+
+@pytest.mark.parametrize("R,M", [(2, 2), (2, 6), (3, 3), (3, 9), (4, 8), (4, 12)])
+def test_interleaved_makespan_for_uniform_action_times(R, M):
+    """With V chunks per rank and equal chunk times f, b the interleaved schedule's bubble is
+    (R - 1)(f + b), a V-th of the non-interleaved one measured in whole-stage times: the batch
+    takes V M (f + b) + (R - 1)(f + b)."""
+    S, V = 2 * R, 2
+    E = sc.pipeline_dag(S, M, I)
+    n = 2 * M * S + 2
+    for f, b in ((1.0, 1.0), (1.0, 2.0), (0.5, 1.75)):
+        w = np.r_[np.full(M * S, f), np.full(M * S, b), 0.0, 0.0]
+        assert sc.start_times(n, E, w)[n - 1] == pytest.approx(V * M * (f + b) + (R - 1) * (f + b))
+
+
+def test_lp_on_a_two_rank_zbv_schedule_against_grid_search():
+    """S = 2 stages on one rank, M = 2 (ZBV with R = 1): the LP's batch time against an exhaustive
+    search over the four backward ratios on a grid."""
+    S, M = 2, 2
+    rs = np.random.default_rng(4)
+    lo = np.r_[rs.uniform(1, 2, M * S), rs.uniform(1, 2, M * S)]
+    hi = lo.copy(); hi[M * S:] += rs.uniform(0.5, 2, M * S)
+    lo[:M * S] = hi[:M * S]
+    sol = sc.freeze_ratio_lp(S, M, Z, lo, hi, 0.5, 1e-6)
+    E = sc.pipeline_dag(S, M, Z)
+    n = 2 * M * S + 2
+    best = np.inf
+    grid = np.linspace(0, 1, 11)
+    for r in itertools.product(grid, repeat=M * S):
+        r = np.array(r)
+        ok = all(np.mean([r[m * S + s] for m in range(M)]) <= 0.5 + 1e-12 for s in range(S))
+        if not ok:
+            continue
+        w = np.r_[hi[:M * S], hi[M * S:] - r * (hi[M * S:] - lo[M * S:]), 0.0, 0.0]
+        best = min(best, sc.start_times(n, E, w)[n - 1])
+    assert sol["P_d"] <= best + 1e-9
+    assert sol["P_d"] >= best - 0.12 * np.max(hi - lo)       # the grid's resolution
