@@ -327,10 +327,15 @@ def lp_example(sweep, tf):
     w_max = np.r_[np.full(S_ * M_, lo), np.full(S_ * M_, hi)]
     w_min = np.r_[np.full(S_ * M_, lo), np.full(S_ * M_, lo)]
     ex = {}
-    for name, sched in (("gpipe", tf.TF_SCHEDULE_GPIPE), ("1f1b", tf.TF_SCHEDULE_1F1B)):
-        sol = tf.tf_freeze_ratio_lp(S_, M_, sched, w_min, w_max, 0.8, 1e-4)
+    for name, sched, per_rank in (("gpipe", tf.TF_SCHEDULE_GPIPE, 1), ("1f1b", tf.TF_SCHEDULE_1F1B, 1),
+                                  ("interleaved_1f1b", tf.TF_SCHEDULE_INTERLEAVED_1F1B, 2), ("zbv", tf.TF_SCHEDULE_ZBV, 2)):
+        # two stages per rank: the same four ranks, every stage half of a measured one
+        n = S_ * per_rank * M_
+        lo_, hi_ = np.r_[w_min[:S_ * M_], w_min[S_ * M_:]] / per_rank, np.r_[w_max[:S_ * M_], w_max[S_ * M_:]] / per_rank
+        sol = tf.tf_freeze_ratio_lp(S_ * per_rank, M_, sched, np.r_[np.full(n, lo_[0]), np.full(n, lo_[-1])],
+                                    np.r_[np.full(n, hi_[0]), np.full(n, hi_[-1])], 0.8, 1e-4)
         ex[name] = {"batch_ms_no_freezing": sol["P_d_max"], "batch_ms_at_r_star": sol["P_d"],
-                    "mean_r_star": float(np.mean(sol["r"][S_ * M_:])),
+                    "mean_r_star": float(np.mean(sol["r"][n:])),
                     "throughput_gain_pct": 100.0 * (sol["P_d_max"] / sol["P_d"] - 1.0)}
     return {"stages": S_, "microbatches": M_, "r_max": 0.8, "lambda": 1e-4, "backward_ms_r0": hi, "backward_ms_r1": lo, **ex}
 

@@ -412,7 +412,20 @@ int tf_reconcile_mask_static(tf_ctx* ctx, void* hip_stream,
  * backward; forward s -> s+1 and backward s+1 -> s of the same microbatch; and
  * the order in which a rank runs its actions - GPipe: all forwards, then all
  * backwards; 1F1B: min(M, S-1-s) forwards, then one forward / one backward in
- * turn, then the remaining backwards.  Writes min(capacity, *n_edges) pairs
+ * turn, then the remaining backwards.  These two keep one stage per rank.
+ * Interleaved 1F1B and ZBV (Sec. 4.2 "Pipeline Schedules") place TWO stages on
+ * each of R = S / 2 ranks (S even, TF_ERR_SHAPE otherwise), and a rank's chain
+ * of edges runs through the actions of both:
+ *   interleaved 1F1B - rank r owns stages r and r + R; it takes g = M / max(1,
+ *     M div R) microbatches per visit of a stage (M must be a multiple of
+ *     max(1, M div R), TF_ERR_SHAPE otherwise), forwards from its first stage
+ *     on, backwards from its last, runs g + 2 (R-1-r) forwards ahead, then
+ *     alternates, then finishes the backwards;
+ *   ZBV - rank r owns stages r and 2R-1-r (V-shaped placement) and follows the
+ *     zero-bubble V schedule; that schedule splits a backward into an
+ *     input-gradient and a weight-gradient pass, the DAG's backward node is
+ *     both and stands where the input-gradient pass runs.
+ * Writes min(capacity, *n_edges) pairs
  * (from, to), sorted, without duplicates; *n_edges is the full count.
  *
  * tf_dag_start_times: P_i = max over predecessors j of (P_j + w_j), 0 for nodes
@@ -433,7 +446,7 @@ int tf_reconcile_mask_static(tf_ctx* ctx, void* hip_stream,
  * tf_actual_freeze_ratio: the progressive ratio of the freezing phase (Sec. 3.3):
  * 0 for t <= T_m, min(r, r (t - T_m) / (T_f - T_m)) after.
  */
-typedef enum { TF_SCHEDULE_GPIPE = 0, TF_SCHEDULE_1F1B = 1 } tf_schedule;
+typedef enum { TF_SCHEDULE_GPIPE = 0, TF_SCHEDULE_1F1B = 1, TF_SCHEDULE_INTERLEAVED_1F1B = 2, TF_SCHEDULE_ZBV = 3 } tf_schedule;
 int tf_pipeline_dag(int32_t n_stages, int32_t n_microbatches, tf_schedule schedule,
                     int32_t capacity, int32_t* edges, int32_t* n_edges);
 int tf_dag_start_times(int32_t n_nodes, int32_t n_edges, const int32_t* edges, const double* w, double* P);

@@ -29,6 +29,8 @@ EXPORTED_SYMBOLS = [
 
 TF_SCHEDULE_GPIPE = 0
 TF_SCHEDULE_1F1B = 1
+TF_SCHEDULE_INTERLEAVED_1F1B = 2
+TF_SCHEDULE_ZBV = 3
 
 KERNEL_KINDS = {0: "dx_mfma", 1: "dw_mfma", 2: "dx_generic", 3: "dw_generic", 4: "adamw", 5: "stability",
                 6: "autofreeze", 7: "reconcile"}

@@ -21,19 +21,98 @@ namespace {
 
 inline int node_id(int a, int m, int s, int M, int S) { return (a * M + m) * S + s; }
 
-// Order in which the rank of stage s runs its 2 M actions.
-std::vector<std::pair<int, int>> rank_order(int s, int M, int S, int schedule) {
-    std::vector<std::pair<int, int>> o;
+struct Act { int a, m, s; };          // forward (0) / backward (1), microbatch, stage
+
+// GPipe and 1F1B keep one stage per rank; interleaved 1F1B and ZBV place two (the training
+// framework's choice for schedules with several stages per rank).
+constexpr int kStagesPerRank = 2;
+
+inline bool one_stage_per_rank(int schedule) { return schedule == TF_SCHEDULE_GPIPE || schedule == TF_SCHEDULE_1F1B; }
+
+// TF_OK, or why (S, M) does not fit the schedule.
+int check_schedule(int S, int M, int schedule) {
+    if (schedule < TF_SCHEDULE_GPIPE || schedule > TF_SCHEDULE_ZBV) return TF_ERR_INVALID_ARG;
+    if (one_stage_per_rank(schedule)) return TF_OK;
+    if (S % kStagesPerRank != 0) return TF_ERR_SHAPE;
+    if (schedule == TF_SCHEDULE_INTERLEAVED_1F1B) {
+        const int R = S / kStagesPerRank, rounds = std::max(1, M / R);
+        if (M % rounds != 0) return TF_ERR_SHAPE;                // a chunk takes M / rounds microbatches per visit
+    }
+    return TF_OK;
+}
+
+// GPipe: all forwards, then all backwards.  1F1B: rank s runs min(M, S - 1 - s) forwards ahead.
+void one_stage_order(int s, int M, int S, int schedule, std::vector<Act>* o) {
     if (schedule == TF_SCHEDULE_GPIPE) {
-        for (int m = 0; m < M; ++m) o.push_back({0, m});
-        for (int m = 0; m < M; ++m) o.push_back({1, m});
-        return o;
+        for (int m = 0; m < M; ++m) o->push_back({0, m, s});
+        for (int m = 0; m < M; ++m) o->push_back({1, m, s});
+        return;
     }
     const int warm = std::min(M, S - 1 - s);                 // forwards before the first backward
-    for (int m = 0; m < warm; ++m) o.push_back({0, m});
-    for (int i = 0; i < M - warm; ++i) { o.push_back({0, warm + i}); o.push_back({1, i}); }
-    for (int m = M - warm; m < M; ++m) o.push_back({1, m});
-    return o;
+    for (int m = 0; m < warm; ++m) o->push_back({0, m, s});
+    for (int i = 0; i < M - warm; ++i) { o->push_back({0, warm + i, s}); o->push_back({1, i, s}); }
+    for (int m = M - warm; m < M; ++m) o->push_back({1, m, s});
+}
+
+// Interleaved 1F1B, rank r of R, V chunks per rank (chunk c is stage c R + r).  A rank visits its
+// chunks in turn, g = M / max(1, M div R) microbatches per visit - forwards from the first chunk
+// on, backwards from the last - so the k-th pass of either kind is visit k / g: chunk (k / g) mod V
+// (mirrored for backwards), microbatch (k / g / V) g + k mod g.  (V - 1) g + 2 (R - 1 - r)
+// forwards run ahead, then forward and backward passes alternate, then the backwards that are left.
+void interleaved_order(int r, int M, int R, std::vector<Act>* o) {
+    const int V = kStagesPerRank;
+    const int g = M / std::max(1, M / R);
+    const int total = V * M;
+    const int warm = std::min((V - 1) * g + 2 * (R - 1 - r), total);
+    auto pass = [&](int a, int k) {
+        const int visit = k / g;
+        const int chunk = a == 0 ? visit % V : V - 1 - visit % V;
+        o->push_back({a, (visit / V) * g + k % g, chunk * R + r});
+    };
+    for (int k = 0; k < warm; ++k) pass(0, k);
+    for (int k = 0; k + warm < total; ++k) { pass(0, warm + k); pass(1, k); }
+    for (int k = total - warm; k < total; ++k) pass(1, k);
+}
+
+// Zero-bubble V schedule, rank r of R: chunk 0 is stage r, chunk 1 stage 2R - 1 - r (the V).  The
+// schedule runs a backward as an input-gradient pass and a weight-gradient pass; a backward node
+// of the DAG is both, placed where the input-gradient pass runs.  It is laid out for
+// n = max(M, 2R - 1) microbatches, those past M left out:
+//   2 (R - r) - 1 forwards of chunk 0;  r x (forward chunk 1, forward chunk 0);
+//   (R - r) x (forward chunk 1, backward chunk 1);
+//   n - R rounds of (forward chunk 0 - the first n - (2R - r - 1) rounds only -, backward chunk 0,
+//   forward chunk 1, backward chunk 1), after which every forward has run;
+//   r x (backward chunk 0, backward chunk 1);  (R - r) x backward chunk 0.
+void zbv_order(int r, int M, int R, std::vector<Act>* o) {
+    const int n = std::max(M, 2 * R - 1);
+    const int stage[2] = {r, 2 * R - 1 - r};
+    int next[2][2] = {{0, 0}, {0, 0}};                       // [a][chunk]: microbatch of the next such pass
+    auto pass = [&](int a, int chunk) {
+        const int m = next[a][chunk]++;
+        if (m < M) o->push_back({a, m, stage[chunk]});
+    };
+    for (int i = 0; i < 2 * (R - r) - 1; ++i) pass(0, 0);
+    for (int i = 0; i < r; ++i) { pass(0, 1); pass(0, 0); }
+    for (int i = 0; i < R - r; ++i) { pass(0, 1); pass(1, 1); }
+    const int rounds = n - R, with_forward0 = n - (2 * R - r - 1);
+    for (int i = 0; i < rounds; ++i) {
+        if (i < with_forward0) pass(0, 0);
+        pass(1, 0); pass(0, 1); pass(1, 1);
+    }
+    for (int i = 0; i < r; ++i) { pass(1, 0); pass(1, 1); }
+    for (int i = 0; i < R - r; ++i) pass(1, 0);
+}
+
+// The order in which every rank runs its actions.
+std::vector<std::vector<Act>> rank_orders(int S, int M, int schedule) {
+    const int R = one_stage_per_rank(schedule) ? S : S / kStagesPerRank;
+    std::vector<std::vector<Act>> all(R);
+    for (int r = 0; r < R; ++r) {
+        if (schedule == TF_SCHEDULE_INTERLEAVED_1F1B) interleaved_order(r, M, R, &all[r]);
+        else if (schedule == TF_SCHEDULE_ZBV) zbv_order(r, M, R, &all[r]);
+        else one_stage_order(r, M, S, schedule, &all[r]);
+    }
+    return all;
 }
 
 std::vector<std::pair<int, int>> build_dag(int S, int M, int schedule) {
@@ -49,10 +128,8 @@ std::vector<std::pair<int, int>> build_dag(int S, int M, int schedule) {
         }
     for (int m = 0; m < M; ++m)                                                 // rule 3
         for (int s = 0; s + 1 < S; ++s) { E.insert({nid(0, m, s), nid(0, m, s + 1)}); E.insert({nid(1, m, s + 1), nid(1, m, s)}); }
-    for (int s = 0; s < S; ++s) {                                               // rule 4: the rank's own order
-        const auto o = rank_order(s, M, S, schedule);
-        for (size_t i = 0; i + 1 < o.size(); ++i) E.insert({nid(o[i].first, o[i].second, s), nid(o[i + 1].first, o[i + 1].second, s)});
-    }
+    for (const auto& o : rank_orders(S, M, schedule))                           // rule 4: each rank's own order
+        for (size_t i = 0; i + 1 < o.size(); ++i) E.insert({nid(o[i].a, o[i].m, o[i].s), nid(o[i + 1].a, o[i + 1].m, o[i + 1].s)});
     return std::vector<std::pair<int, int>>(E.begin(), E.end());
 }
 
@@ -157,8 +234,9 @@ extern "C" {
 int tf_pipeline_dag(int32_t n_stages, int32_t n_microbatches, tf_schedule schedule,
                     int32_t capacity, int32_t* edges, int32_t* n_edges) {
     if (n_stages <= 0 || n_microbatches <= 0 || capacity < 0 || !n_edges) return TF_ERR_INVALID_ARG;
-    if (schedule != TF_SCHEDULE_GPIPE && schedule != TF_SCHEDULE_1F1B) return TF_ERR_INVALID_ARG;
     if (int64_t(n_stages) * n_microbatches > (1 << 20)) return TF_ERR_SHAPE;
+    const int fit = check_schedule(n_stages, n_microbatches, schedule);
+    if (fit != TF_OK) return fit;
     const auto E = build_dag(n_stages, n_microbatches, schedule);
     *n_edges = int32_t(E.size());
     if (capacity > 0 && !edges) return TF_ERR_INVALID_ARG;
@@ -183,9 +261,10 @@ int tf_freeze_ratio_lp(int32_t S, int32_t M, tf_schedule schedule,
                        const double* w_min, const double* w_max, double r_max, double lambda,
                        double* r, double* w, double* P, double* batch_time_max, double* batch_time) {
     if (S <= 0 || M <= 0 || !w_min || !w_max || !r) return TF_ERR_INVALID_ARG;
-    if (schedule != TF_SCHEDULE_GPIPE && schedule != TF_SCHEDULE_1F1B) return TF_ERR_INVALID_ARG;
     if (!(r_max >= 0.0 && r_max <= 1.0) || !(lambda >= 0.0 && lambda < 1.0)) return TF_ERR_INVALID_ARG;
     if (int64_t(S) * M > 4096) return TF_ERR_SHAPE;                            // dense tableau: small schedules only
+    const int fit = check_schedule(S, M, schedule);
+    if (fit != TF_OK) return fit;
     const int n_act = 2 * M * S, N = n_act + 2, src = n_act, dst = n_act + 1;
     double scale = 0.0;
     for (int i = 0; i < n_act; ++i) {

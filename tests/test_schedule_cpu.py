@@ -9,7 +9,10 @@ import pytest
 import paper_2602_05754_amd as tf
 from oracle import schedule as sc
 
-CASES = [(1, 1, 0), (1, 3, 1), (2, 2, 0), (2, 2, 1), (3, 2, 1), (2, 5, 0), (4, 8, 0), (4, 8, 1), (8, 8, 1), (3, 7, 1)]
+CASES = [(1, 1, 0), (1, 3, 1), (2, 2, 0), (2, 2, 1), (3, 2, 1), (2, 5, 0), (4, 8, 0), (4, 8, 1), (8, 8, 1), (3, 7, 1),
+         # interleaved 1F1B (2) and ZBV (3): two stages per rank
+         (2, 1, 2), (2, 3, 2), (4, 2, 2), (4, 4, 2), (6, 3, 2), (6, 9, 2), (8, 8, 2), (8, 4, 2), (8, 3, 2), (10, 15, 2),
+         (2, 1, 3), (2, 3, 3), (4, 2, 3), (4, 5, 3), (6, 4, 3), (6, 2, 3), (8, 8, 3), (8, 2, 3), (8, 13, 3), (10, 7, 3)]
 
 
 @pytest.mark.parametrize("S,M,sched", CASES)
@@ -34,6 +37,13 @@ def test_start_times_reject_cycles_and_bad_input():
         tf.tf_pipeline_dag(0, 2, 0)
     with pytest.raises(tf.TfError):
         tf.tf_pipeline_dag(2, 2, 5)
+    for sched in (tf.TF_SCHEDULE_INTERLEAVED_1F1B, tf.TF_SCHEDULE_ZBV):
+        with pytest.raises(tf.TfError) as e:
+            tf.tf_pipeline_dag(3, 2, sched)                          # two stages per rank: an odd stage count
+        assert e.value.code == -2
+    with pytest.raises(tf.TfError) as e:
+        tf.tf_pipeline_dag(4, 5, tf.TF_SCHEDULE_INTERLEAVED_1F1B)    # 5 microbatches on 2 ranks: not whole rounds
+    assert e.value.code == -2
 
 
 def _times(S, M, seed, frac=(0.4, 0.7)):
@@ -48,7 +58,8 @@ def _times(S, M, seed, frac=(0.4, 0.7)):
     return w_min, w_max
 
 
-@pytest.mark.parametrize("S,M,sched", [(2, 2, 0), (2, 2, 1), (3, 2, 1), (2, 4, 0), (4, 8, 0), (4, 8, 1), (4, 4, 1), (6, 8, 1)])
+@pytest.mark.parametrize("S,M,sched", [(2, 2, 0), (2, 2, 1), (3, 2, 1), (2, 4, 0), (4, 8, 0), (4, 8, 1), (4, 4, 1), (6, 8, 1),
+                                       (4, 4, 2), (8, 8, 2), (8, 4, 2), (4, 3, 3), (8, 8, 3), (6, 5, 3)])
 def test_freeze_ratio_lp_against_the_oracle(S, M, sched):
     lam = 1e-4
     n_act = 2 * M * S
