@@ -102,26 +102,52 @@ __host__ __device__ __forceinline__ int logical_tile(int b, int nb, int grid) {
     return ((idx / kXcdRun) * kXcds + xcd) * kXcdRun + idx % kXcdRun;
 }
 
-struct TilePos { int pi, m0, n0; };
+struct TilePos {
+    int pi, m0, n0;            // problem; origin of the 256 x 256 window the tile computes
+    // The part of the window that is this tile's to store: rows [r_lo, r_hi), columns [c_lo, c_hi)
+    // of the window, (0, 256) x (0, 256) except in a problem's last tile row / column.
+    int r_lo, r_hi, c_lo, c_hi;
+    __device__ bool whole() const { return r_lo == 0 && r_hi == kBM && c_lo == 0 && c_hi == kBN; }
+};
 
-// Logical tile -> problem and tile origin.  `pi` is where the search starts: a workgroup
+// One dimension of a problem whose extent is not a multiple of the tile edge: where the window
+// of its last tile starts and which part of it is stored.  The window is always 256 wide and
+// only ever covers operand rows that exist in memory: it is moved back so that it ends with the
+// problem (overlapping the tile before it, whose outputs it computes again and does not store);
+// a problem narrower than one window may instead run over its end, or start before its
+// beginning, by as many rows as the host has said exist there (`before`, `after`).
+__device__ __forceinline__ void edge_window(int extent, int tile, int before, int after, int& origin, int& lo, int& hi) {
+    origin = tile * kBM; lo = 0; hi = kBM;
+    const int missing = origin + kBM - extent;
+    if (missing <= 0) return;
+    if (after >= missing) { hi = kBM - missing; return; }       // reads past the problem's end, stores what is inside
+    origin -= missing;                                          // ends with the problem (origin >= -before)
+    lo = missing;
+}
+
+// Logical tile -> problem and tile window.  `pi` is where the search starts: a workgroup
 // visits its tiles in increasing order, so the problem index never goes back.
 __device__ __forceinline__ TilePos locate_tile(const GemmBatch& batch, int lt, int pi) {
     while (pi + 1 < batch.n_problems && lt >= batch.p[pi + 1].tile_start) ++pi;
     const GemmProblem& P = batch.p[pi];
-    const int tiles_m = P.M / kBM, tiles_n = P.N / kBN;
+    const int tiles_m = (P.M + kBM - 1) / kBM, tiles_n = (P.N + kBN - 1) / kBN;
     int t = lt - P.tile_start;
     const int per_group = kGroupM * tiles_n;
     const int first_m = (t / per_group) * kGroupM;
     const int gsz = min(tiles_m - first_m, kGroupM);
     t %= per_group;
     int row = first_m + t % gsz;                      // tile row among the rows that exist
-    if (~P.row_bits != 0) {                           // the row-th set bit is the actual 256-row block
+    TilePos tp;
+    tp.pi = pi;
+    if (~P.row_bits != 0) {                           // the row-th set bit is the actual 256-row block (whole tiles only)
         uint64_t b = P.row_bits;
         for (int q = 0; q < row; ++q) b &= b - 1;
-        row = __ffsll(static_cast<long long>(b)) - 1;
+        tp.m0 = (__ffsll(static_cast<long long>(b)) - 1) * kBM; tp.r_lo = 0; tp.r_hi = kBM;
+    } else {
+        edge_window(P.M, row, P.m_slack & 0xffff, P.m_slack >> 16, tp.m0, tp.r_lo, tp.r_hi);
     }
-    return TilePos{pi, row * kBM, (t / gsz) * kBN};
+    edge_window(P.N, t / gsz, 0, 0, tp.n0, tp.c_lo, tp.c_hi);
+    return tp;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -345,9 +371,11 @@ __device__ __forceinline__ bf16x8 load_frag(const char* stage, int addr, int u) 
 // A lane's values are scattered over the block, so the wave turns 8 KB pieces around in its
 // own LDS area `wlds` (32 rows of 256 bytes) and writes whole 256-byte row segments.
 // ---------------------------------------------------------------------------------------------
-template <bool kOutBf16, bool kAccumulate, int kAhead>
+// kEdge: only rows [r_lo, r_hi) and columns [c_lo, c_hi) of the wave's 128 x 128 block are stored
+// (and, when accumulating, read): the tile is the last of its problem in some direction.
+template <bool kOutBf16, bool kAccumulate, int kAhead, bool kEdge>
 __device__ __forceinline__ void store_block(const f32x4 (&acc)[8][8], char* wlds, void* C, int64_t N,
-                                            int row0, int col0) {
+                                            int row0, int col0, int r_lo = 0, int r_hi = 128, int c_lo = 0, int c_hi = 128) {
     int lane = threadIdx.x & 63;
     // The epilogue sits inside the tile loop.  Its per-lane addresses are loop invariants, and
     // kept in registers across the contraction steps they would crowd out the operands: make
@@ -364,6 +392,7 @@ __device__ __forceinline__ void store_block(const f32x4 (&acc)[8][8], char* wlds
         // pace.  The stores are non-temporal: the output is not read again by this kernel, and
         // left in L2 it would push out the operand panels that the other workgroups still fetch.
         uint16_t* Cw = static_cast<uint16_t*>(C) + int64_t(row0) * N + col0 + cb * 8;
+        const bool col_ok = !kEdge || (cb * 8 >= c_lo && cb * 8 < c_hi);         // a lane's 8 columns: all or none
         U2 pk[16];                         // one pass, rounded: pk[8 h + j] is chunk 4 j + lq of row 16 h + lrow
         auto round_piece = [&](int ps, int k) {     // two of the sixteen chunks of pass ps
 #pragma unroll
@@ -401,7 +430,8 @@ __device__ __forceinline__ void store_block(const f32x4 (&acc)[8][8], char* wlds
             for (int it = 0; it < 8; ++it) {
                 const int m = it * 4 + rsub;
                 const U4 w = (m & 1) ? U4{v[it].z, v[it].w, v[it].x, v[it].y} : v[it];
-                __builtin_nontemporal_store(w, reinterpret_cast<U4*>(Cw + int64_t(i * 32 + m) * N));
+                if (!kEdge || (col_ok && i * 32 + m >= r_lo && i * 32 + m < r_hi))
+                    __builtin_nontemporal_store(w, reinterpret_cast<U4*>(Cw + int64_t(i * 32 + m) * N));
                 if (i < 3) round_piece(i + 1, it);
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -414,19 +444,25 @@ __device__ __forceinline__ void store_block(const f32x4 (&acc)[8][8], char* wlds
         // retention (non-temporal) for the same reason as above.
         float* Cw = static_cast<float*>(C) + int64_t(row0) * N + col0 + cb * 4;
         auto gaddr = [&](int p, int it) { return Cw + int64_t((p >> 1) * 32 + it * 4 + rsub) * N + (p & 1) * 64; };
-        constexpr int kRing = kAhead + 1;
+        auto mine = [&](int p, int it) {           // is this lane's 4-column piece of pass p, step it, to be stored?
+            const int r = (p >> 1) * 32 + it * 4 + rsub, c = (p & 1) * 64 + cb * 4;
+            return !kEdge || (r >= r_lo && r < r_hi && c >= c_lo && c < c_hi);
+        };
+        // (an edge tile fetches each old value right where it is used: no ring of registers)
+        constexpr bool kPrefetch = kAccumulate && !kEdge;
+        constexpr int kRing = kPrefetch ? kAhead + 1 : 1;
         F4 old[kRing][8];
         auto fetch_old = [&](int p) {
 #pragma unroll
             for (int it = 0; it < 8; ++it) old[p % kRing][it] = __builtin_nontemporal_load(reinterpret_cast<const F4*>(gaddr(p, it)));
         };
-        if (kAccumulate) {
+        if (kPrefetch) {
 #pragma unroll
             for (int p = 0; p < kAhead; ++p) fetch_old(p);
         }
 #pragma unroll
         for (int p = 0; p < 8; ++p) {
-            if (kAccumulate && p + kAhead < 8) fetch_old(p + kAhead);
+            if (kPrefetch && p + kAhead < 8) fetch_old(p + kAhead);
             const int ps = p >> 1, jh = p & 1;
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -441,8 +477,11 @@ __device__ __forceinline__ void store_block(const f32x4 (&acc)[8][8], char* wlds
             for (int it = 0; it < 8; ++it) {
                 const int m = it * 4 + rsub;
                 F4 v = *reinterpret_cast<const F4*>(wlds + m * 256 + ((cb ^ (m & 15)) << 4));
-                if (kAccumulate) v += old[p % kRing][it];
-                __builtin_nontemporal_store(v, reinterpret_cast<F4*>(gaddr(p, it)));
+                if (kPrefetch) v += old[p % kRing][it];
+                if (mine(p, it)) {
+                    if (kAccumulate && kEdge) v += __builtin_nontemporal_load(reinterpret_cast<const F4*>(gaddr(p, it)));
+                    __builtin_nontemporal_store(v, reinterpret_cast<F4*>(gaddr(p, it)));
+                }
             }
         }
     }
@@ -708,7 +747,14 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
         // The deep stage that the last step consumed (d2 after the rotation) is the epilogue's:
         // every wave is past that step's barrier, and its next fill is issued by the next step.
         const GemmProblem& P = batch.p[ct.pi];
-        store_block<kOutBf16, kAccumulate, kTN ? 2 : 1>(acc, lds + d2 + wave * kEpiBytes, P.C, P.N, ct.m0 + wm * 128, ct.n0 + wn * 128);
+        if (__builtin_expect(ct.whole(), 1))
+            store_block<kOutBf16, kAccumulate, kTN ? 2 : 1, false>(acc, lds + d2 + wave * kEpiBytes, P.C, P.N,
+                                                                   ct.m0 + wm * 128, ct.n0 + wn * 128);
+        else
+            store_block<kOutBf16, kAccumulate, 1, true>(acc, lds + d2 + wave * kEpiBytes, P.C, P.N,
+                                                                  ct.m0 + wm * 128, ct.n0 + wn * 128,
+                                                                  ct.r_lo - wm * 128, ct.r_hi - wm * 128,
+                                                                  ct.c_lo - wn * 128, ct.c_hi - wn * 128);
         cvb += stride;
         if (cvb >= total) break;
         __syncthreads();          // no wave may fill that stage while another still turns its block around in it
@@ -779,12 +825,16 @@ extern "C" int tf_internal_tile_order(int total_tiles, int units, int32_t* out) 
 
 namespace tf {
 
-bool mfma_shape_ok(int64_t M, int64_t N, int64_t Kc, int64_t lda, int64_t ldb) {
-    // 16-byte direct loads: row pitches must keep every row 16-byte aligned
-    // and 256 rows of either operand must lie within the 32-bit per-lane offsets of a stage fill
+bool mfma_shape_ok(Layout layout, int64_t M, int64_t N, int64_t Kc, int64_t lda, int64_t ldb,
+                   int64_t rows_before, int64_t rows_after) {
+    // 16-byte direct loads and 16-byte stores: row pitches (C's is N) must keep every row 16-byte
+    // aligned, and 256 rows of either operand must lie within the 32-bit per-lane offsets of a stage fill
     constexpr int64_t kMaxPitch = int64_t(1) << 22;
-    return M > 0 && N > 0 && Kc > 0 && M % kBM == 0 && N % kBN == 0 && Kc % kBK == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
-           lda <= kMaxPitch && ldb <= kMaxPitch;
+    if (!(M > 0 && N >= kBN && Kc > 0 && Kc % kBK == 0 && N % 8 == 0 && lda % 8 == 0 && ldb % 8 == 0 &&
+          lda <= kMaxPitch && ldb <= kMaxPitch))
+        return false;
+    if (layout == Layout::kTN && M % 8 != 0) return false;           // a window's first column of A stays 16-byte aligned
+    return M >= kBM || rows_before + rows_after >= kBM - M;          // a 256-row window must fit into what exists
 }
 
 hipError_t launch_gemm_mfma_bf16(hipStream_t stream, GemmBatch& batch, int n_problems,
@@ -794,9 +844,9 @@ hipError_t launch_gemm_mfma_bf16(hipStream_t stream, GemmBatch& batch, int n_pro
     const bool tn = layout == Layout::kTN;
     if (out_dtype == Dtype::BF16)
         return tn ? launch_one<true, true, false>(stream, batch) : launch_one<false, true, false>(stream, batch);
-    if (accumulate)
-        return tn ? launch_one<true, false, true>(stream, batch) : launch_one<false, false, true>(stream, batch);
-    return tn ? launch_one<true, false, false>(stream, batch) : launch_one<false, false, false>(stream, batch);
+    // fp32 outputs are weight gradients (an input gradient has the inputs' type)
+    if (!tn) return hipErrorInvalidValue;
+    return accumulate ? launch_one<true, false, true>(stream, batch) : launch_one<true, false, false>(stream, batch);
 }
 
 }  // namespace tf

@@ -97,6 +97,7 @@ struct Planned {
     // further contraction segments whose products are summed into the same C (layers that
     // share their input); matrix-core kernel only
     std::vector<Planned> more;
+    int64_t rows_before = 0, rows_after = 0;   // operand rows in memory around the problem's own (sub-tensor problems)
 
     int64_t total_kc() const {
         int64_t k = Kc;
@@ -105,8 +106,8 @@ struct Planned {
     }
 };
 
-inline bool planned_mfma_ok(const Planned& it, Dtype in_dtype) {
-    return in_dtype == Dtype::BF16 && mfma_shape_ok(it.M, it.N, it.Kc, it.lda, it.ldb) &&
+inline bool planned_mfma_ok(const Planned& it, Layout layout, Dtype in_dtype) {
+    return in_dtype == Dtype::BF16 && mfma_shape_ok(layout, it.M, it.N, it.Kc, it.lda, it.ldb, it.rows_before, it.rows_after) &&
            aligned16(it.A) && aligned16(it.B) && aligned16(it.C);
 }
 
@@ -116,8 +117,8 @@ hipError_t launch_planned(tf_ctx* ctx, hipStream_t stream, std::vector<Planned>&
                           Dtype in_dtype, Dtype out_dtype, bool accumulate) {
     std::vector<Planned> fast, slow;
     for (const Planned& it : items) {
-        bool ok = planned_mfma_ok(it, in_dtype);
-        for (const Planned& q : it.more) ok = ok && planned_mfma_ok(q, in_dtype);
+        bool ok = planned_mfma_ok(it, layout, in_dtype);
+        for (const Planned& q : it.more) ok = ok && planned_mfma_ok(q, layout, in_dtype);
         if (ok) fast.push_back(it);
         else if (~it.row_bits != 0 || !it.more.empty()) return hipErrorInvalidValue;   // only the matrix-core kernel knows these
         else slow.push_back(it);
@@ -133,7 +134,11 @@ hipError_t launch_planned(tf_ctx* ctx, hipStream_t stream, std::vector<Planned>&
         gp.M = int32_t(it.M); gp.N = int32_t(it.N); gp.Kc = int32_t(it.Kc);
         gp.lda = int32_t(it.lda); gp.ldb = int32_t(it.ldb); gp.row_bits = it.row_bits;
         gp.tile_start = int32_t(tile_start);
-        gp.n_seg = n_seg; gp.pad_ = 0;
+        gp.n_seg = n_seg;
+        // a problem narrower than one tile window: prefer running over its end to starting before its beginning
+        const int64_t short_by = it.M < gemm_mfma_tile() ? gemm_mfma_tile() - it.M : 0;
+        const int64_t after = std::min(it.rows_after, short_by), before = std::min(it.rows_before, short_by - after);
+        gp.m_slack = uint32_t(before) | (uint32_t(after) << 16);
     };
     for (int pass = 0; pass < 2; ++pass) {
         const std::vector<Planned>& v = pass == 0 ? fast : slow;
@@ -416,8 +421,8 @@ int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
         }
         for (const Planned& it : plan) {
             if (it.more.empty()) continue;
-            bool ok = planned_mfma_ok(it, in_dt);
-            for (const Planned& q : it.more) ok = ok && planned_mfma_ok(q, in_dt);
+            bool ok = planned_mfma_ok(it, Layout::kNT, in_dt);
+            for (const Planned& q : it.more) ok = ok && planned_mfma_ok(q, Layout::kNT, in_dt);
             if (!ok) grouped_slow = true;
         }
     }
@@ -457,7 +462,7 @@ int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
         // blocks (a bit per block), so that any pattern of frozen blocks costs one problem.
         const int64_t tile = gemm_mfma_tile();
         if (in_dt == Dtype::BF16 && block_rows % tile == 0 && K / tile <= 64 &&
-            mfma_shape_ok(tile, N, T, K, N) && aligned16(X[l]) && aligned16(dY[l]) && aligned16(dW[l])) {
+            mfma_shape_ok(Layout::kTN, tile, N, T, K, N) && aligned16(X[l]) && aligned16(dY[l]) && aligned16(dW[l])) {
             uint64_t bits = 0;
             int64_t rows = 0;
             const int64_t per = block_rows / tile;
@@ -474,8 +479,11 @@ int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
             int64_t e1 = b;
             while (e1 < nb && !rm[e1]) ++e1;
             const int64_t k0 = b * block_rows, rows = (e1 - b) * block_rows;
-            plan.push_back(Planned{static_cast<const char*>(X[l]) + k0 * in_size, dY[l],
-                                   static_cast<char*>(dW[l]) + k0 * N * dw_size, rows, N, T, K, N, ~0ull, {}});
+            Planned run{static_cast<const char*>(X[l]) + k0 * in_size, dY[l],
+                        static_cast<char*>(dW[l]) + k0 * N * dw_size, rows, N, T, K, N, ~0ull, {}};
+            run.rows_before = k0;                    // columns of X on either side of the run's own
+            run.rows_after = K - k0 - rows;
+            plan.push_back(run);
             b = e1;
         }
     }

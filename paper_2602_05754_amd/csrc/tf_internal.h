@@ -37,7 +37,11 @@ struct GemmProblem {
     // C = sum over the segments of A_i B_i^T - several layers that share their input give ONE
     // input gradient, accumulated in fp32 and rounded once.  1 = an ordinary problem.
     int32_t n_seg;
-    int32_t pad_;
+    // MFMA kernel only, for a problem with fewer than 256 rows: operand rows that exist in memory
+    // before row 0 (low 16 bits) and after row M - 1 (high 16 bits), each at most 256.  Its one
+    // tile computes a 256-row window that runs over the problem's end or starts before its
+    // beginning by that much, and stores only the problem's rows.  0 for M >= 256.
+    uint32_t m_slack;
 };
 
 constexpr int kMaxProblemsPerLaunch = 64;
@@ -53,9 +57,12 @@ struct GemmBatch {          // passed by value as the kernel argument (64 x 64 B
 hipError_t launch_gemm_generic(hipStream_t stream, GemmBatch& batch, int n_problems,
                                Layout layout, Dtype in_dtype, Dtype out_dtype, bool accumulate);
 
-// MFMA kernel for bf16 inputs.  Requires M % 256 == 0, N % 256 == 0, Kc % 64 == 0
-// for every problem in the batch (mfma_shape_ok).
-bool mfma_shape_ok(int64_t M, int64_t N, int64_t Kc, int64_t lda, int64_t ldb);
+// MFMA kernel for bf16 inputs.  What it takes (mfma_shape_ok): contraction a multiple of 64; output
+// columns N >= 256 and a multiple of 8; output rows M >= 256, or fewer with rows_before +
+// rows_after >= 256 - M operand rows in memory around them; layout kTN also M a multiple of 8; row
+// pitches multiples of 8 and at most 2^22.  Extents need not be multiples of the 256 x 256 tile.
+bool mfma_shape_ok(Layout layout, int64_t M, int64_t N, int64_t Kc, int64_t lda, int64_t ldb,
+                   int64_t rows_before = 0, int64_t rows_after = 0);
 hipError_t launch_gemm_mfma_bf16(hipStream_t stream, GemmBatch& batch, int n_problems,
                                  Layout layout, Dtype out_dtype, bool accumulate);
 int gemm_generic_tile();          // tile edge of the generic kernel (square)
