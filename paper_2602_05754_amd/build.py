@@ -15,6 +15,7 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
     "-Wall", "-Wno-unused-command-line-argument",
+    "-Wno-inline-asm",          # the direct-to-LDS loads name M0 in their clobber list on purpose
     "-Rpass-analysis=kernel-resource-usage",      # per-kernel register / scratch report, checked below
 ]
 
@@ -36,7 +37,7 @@ def scc_hazards(asm_text: str) -> list:
     say, the s_add_u32 and the s_addc_u32 of a 64-bit address addition; a lost carry there is
     a wild global address.  This scan of the generated code is the belt to those braces: it
     walks every function linearly and reports each reader of SCC whose nearest preceding
-    scalar instruction that writes SCC lies before an inline-assembly block.
+    scalar instruction that writes SCC lies before an inline-assembly block that sets SCC itself.
     Returns a list of (function, line number, instruction)."""
     bad = []
     func = None
@@ -52,12 +53,17 @@ def scc_hazards(asm_text: str) -> list:
             continue
         if "#ASMSTART" in line:
             in_asm = True
-            asm_since_write = True
             continue
         if "#ASMEND" in line:
             in_asm = False
             continue
-        if in_asm or not line.startswith("s_"):
+        if in_asm:
+            # only assembly that itself sets SCC can lose a carry (a vector addition without carry,
+            # a plain move or a load leaves it alone)
+            if line.startswith("s_") and not _SCC_KEEPERS.match(line.split()[0]):
+                asm_since_write = True
+            continue
+        if not line.startswith("s_"):
             continue
         op = line.split()[0]
         if _SCC_READERS.match(op) and asm_since_write:

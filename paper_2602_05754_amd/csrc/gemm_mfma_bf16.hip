@@ -487,6 +487,56 @@ __device__ __forceinline__ void store_block(const f32x4 (&acc)[8][8], char* wlds
     }
 }
 
+// The same fetch in two halves, for the contraction loop: the LDS address of a fragment (stage
+// address, a scalar that changes from step to step, plus the lane's offset) is formed one MFMA
+// slot before the read that uses it.  Measured with MFMAs issuing back to back: a vector
+// addition followed at once by the LDS read that depends on it holds the wave for 8 cycles
+// beyond what the MFMA in flight covers, the read alone for none - with 32 reads per step that
+// was a tenth of the step.
+template <bool kTN>
+__device__ __forceinline__ uint32_t frag_address(uint32_t stage_lds, int addr, int u) {
+    uint32_t r;
+    const int off = kTN ? addr : (addr ^ (u << 6));
+    asm volatile("v_add_u32 %0, %1, %2" : "=v"(r) : "s"(stage_lds), "v"(off));
+    return r;
+}
+template <bool kTN>
+__device__ __forceinline__ bf16x8 read_frag(uint32_t a, int u) {
+    typedef __attribute__((address_space(3))) const bf16x8* LdsBf16x8Ptr;
+    if (kTN) {
+        const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LdsBf16x4Ptr)(uintptr_t)(a + (32 * u) * 512));
+        const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LdsBf16x4Ptr)(uintptr_t)(a + (32 * u + 4) * 512));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    } else {
+        return *(LdsBf16x8Ptr)(uintptr_t)a;
+    }
+}
+
+// Which operand fragment is read from LDS behind MFMA slot (u, i, jj) of a contraction step.
+struct FragRead {
+    int op;       // 0 none, 1 an A fragment, 2 a B fragment
+    int next;     // 0 this step's stages, 1 the next step's (after the stage barrier)
+    int idx;      // 16-row block
+    int u;        // sub-step whose operand it is (for a B fragment also the buffer it goes to)
+};
+__device__ __forceinline__ constexpr FragRead frag_read_at(int u, int i, int jj) {
+    // A operand 7 of this very sub-step: its registers were busy until the last row of the
+    // sub-step before
+    if (i == 0 && jj == 0) return {1, 0, 7, u};
+    if (u == 0) {
+        // next sub-step, same stage
+        if (i >= 1 && jj == 0) return {1, 0, i - 1, 1};
+        if (jj == 4) return {2, 0, i, 1};
+    } else if (i >= 4) {
+        // first sub-step of the next step, after the barrier
+        if (i == 4 && !(jj & 1)) return {1, 1, jj >> 1, 0};
+        if (i >= 5 && jj == 0) return {1, 1, i - 1, 0};
+        if (jj == 1) return {2, 1, 2 * (i - 4), 0};
+        if (jj == 5) return {2, 1, 2 * (i - 4) + 1, 0};
+    }
+    return {0, 0, 0, 0};
+}
+
 template <bool kTN, bool kOutBf16, bool kAccumulate>
 __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -497,8 +547,8 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
 
     // LDS byte address of the dynamic shared array (a 32-bit LDS pointer is its byte offset),
     // plus this wave's 1 KB slot inside every group of 4 KB of a stage fill.
-    const uint32_t lds_wave_base = __builtin_amdgcn_readfirstlane(
-        uint32_t(reinterpret_cast<uintptr_t>(TF_LPTR(lds))) + uint32_t(wave) * 1024u);
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane(uint32_t(reinterpret_cast<uintptr_t>(TF_LPTR(lds))));
+    const uint32_t lds_wave_base = lds_base + __builtin_amdgcn_readfirstlane(uint32_t(wave) * 1024u);
     const FragAddr fr = make_frag_addr<kTN>(wm, wn);
 
     // Fill stream.  The deep operand (B) of step g goes to deep stage g % 3, the shallow operand
@@ -607,6 +657,11 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     auto stage_a = [&](uint32_t, uint32_t sh) { return lds + sh; };     // A is the shallow operand
     auto stage_b = [&](uint32_t d, uint32_t) { return lds + d; };       // B the deep one
 
+    // LDS address of the fragment that the next read fetches (see frag_address): formed behind one
+    // MFMA, used behind the next; the one for a step's first read is formed in the last slot of the
+    // step before it (here: for the first step).
+    uint32_t frag_at = frag_address<kTN>(lds_base + s0, fr.a[7], 0);
+
     // 8 x 8 accumulator tiles of 16 x 16.  A sub-step (32 of the contraction) is 64 MFMAs, row by
     // row of tiles.  The A operands live in one set of registers: operand i of the next sub-step is
     // read as soon as row i of this one has been issued.  The B operands are needed by every row
@@ -642,10 +697,8 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
     // 4 cycles and an MFMA occupies the matrix pipe for 16: three other instructions fit behind it.
     auto contraction_step = [&](auto first_tag) {
         constexpr bool kFirst = decltype(first_tag)::value;
-        const char* cur_a = stage_a(d0, s0);
-        const char* cur_b = stage_b(d0, s0);
-        const char* nxt_a = stage_a(d1, s1);
-        const char* nxt_b = stage_b(d1, s1);
+        // LDS addresses of this step's stages and the next step's: A is the shallow operand, B the deep one
+        const uint32_t stage_lds[2][2] = {{lds_base + s0, lds_base + d0}, {lds_base + s1, lds_base + d1}};
         const uint32_t deep_fill = lds_wave_base + d2;
         const uint32_t shallow_fill = lds_wave_base + s0;
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -673,20 +726,19 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
                     acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[u][j], fa[i],
                                                                        (kFirst && u == 0) ? zero : acc[i][j], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);          // the MFMA first, then what rides behind it
-                    // --- operand reads ---
-                    // A operand 7 of this very sub-step: its registers were busy until the last row
-                    // of the sub-step before
-                    if (i == 0 && jj == 0) fa[7] = load_frag<kTN>(cur_a, fr.a[7], u);
-                    if (u == 0) {
-                        // next sub-step, same stage
-                        if (i >= 1 && jj == 0) fa[i - 1] = load_frag<kTN>(cur_a, fr.a[i - 1], 1);
-                        if (jj == 4) fb[1][i] = load_frag<kTN>(cur_b, fr.b[i], 1);
-                    } else if (i >= 4) {
-                        // first sub-step of the next step, after the barrier
-                        if (i == 4 && !(jj & 1)) fa[jj >> 1] = load_frag<kTN>(nxt_a, fr.a[jj >> 1], 0);
-                        if (i >= 5 && jj == 0) fa[i - 1] = load_frag<kTN>(nxt_a, fr.a[i - 1], 0);
-                        if (jj == 1) fb[0][2 * (i - 4)] = load_frag<kTN>(nxt_b, fr.b[2 * (i - 4)], 0);
-                        if (jj == 5) fb[0][2 * (i - 4) + 1] = load_frag<kTN>(nxt_b, fr.b[2 * (i - 4) + 1], 0);
+                    // --- operand reads: this slot's read, from the address formed one slot ago; then
+                    // the address for the next slot's (the slot after the step's last one is the next
+                    // step's first, whose stages are this step's next ones) ---
+                    {
+                        const FragRead rd = frag_read_at(u, i, jj);
+                        if (rd.op == 1) fa[rd.idx] = read_frag<kTN>(frag_at, rd.u);
+                        if (rd.op == 2) fb[rd.u][rd.idx] = read_frag<kTN>(frag_at, rd.u);
+                        const int sl = (u * 64 + i * 8 + jj + 1) % 128;
+                        const bool wrap = u == 1 && i == 7 && jj == 7;
+                        const FragRead nx = frag_read_at(sl >> 6, (sl >> 3) & 7, sl & 7);
+                        if (nx.op != 0)
+                            frag_at = frag_address<kTN>(stage_lds[wrap ? 1 : nx.next][nx.op - 1],
+                                                        nx.op == 1 ? fr.a[nx.idx] : fr.b[nx.idx], nx.u);
                     }
                     // --- stage fills: one load after every fourth MFMA, the rate at which the
                     // texture-address unit, which the waves share, takes them ---

@@ -198,8 +198,20 @@ kernel_c:
 	s_mov_b32 s7, s8
 	s_cbranch_scc1 .LBB0_1
 """
+    harmless_assembly = """
+kernel_d:
+	s_add_u32 s0, s1, s2
+	;;#ASMSTART
+	v_add_u32 v9, s3, v8
+	;;#ASMEND
+	;;#ASMSTART
+	s_mov_b32 s11, s12
+	;;#ASMEND
+	s_addc_u32 s4, s5, 0
+"""
     assert [(f, ins.split()[0]) for f, _, ins in scc_hazards(split_carry)] == [("kernel_a", "s_addc_u32")]
     assert scc_hazards(fine) == []
+    assert scc_hazards(harmless_assembly) == []        # assembly that leaves SCC alone may sit anywhere
     assert [(f, ins.split()[0]) for f, _, ins in scc_hazards(branch_on_stale)] == [("kernel_c", "s_cbranch_scc1")]
 
 
