@@ -26,14 +26,31 @@ constexpr int kThreads = 256;
 // ------------------------------------------------------------------------------------------
 // AutoFreeze norms
 // ------------------------------------------------------------------------------------------
-// 8 iterations of 16 bytes per array and thread measured 13 % faster than 4 (and 2 much slower)
-constexpr int kNormGroup = 4, kNormIters = 8;
-constexpr int64_t kNormElemsPerBlock = int64_t(kThreads) * kNormGroup * kNormIters;
+// The launch shape follows the fused optimizer pass (what decides the rate is how the three
+// streams meet in the memory system): a block is ONE wave and each of its accesses is 1 KB of one
+// array (whole 128-byte lines); an unused 8 KB of dynamic LDS per block caps a compute unit at 20
+// blocks; every access is non-temporal.  Measured on the 8B stage's 1.74e9 elements: 6.6 TB/s
+// with 2 iterations per block and 20 blocks per unit (1 iteration: 5.4; 4: 6.5; 8: 5.9; 10 blocks
+// per unit: 4.7 .. 6.1), against 5.5 for blocks of four waves and 8 iterations.
+// With 3.4 million blocks the per-tensor sums are gathered in two levels like the optimizer's
+// score sums: a block adds to one of 64 slots of its tensor, a second kernel adds up the slots.
+constexpr int kNormThreads = 64;
+constexpr int kNormGroup = 4, kNormIters = 2;
+constexpr int kNormResidencyLds = 8192;
+constexpr int kNormSlotDouble = 2;          // which double of a 64-byte slot (0 and 1 are the optimizer's)
+constexpr int64_t kNormElemsPerBlock = int64_t(kNormThreads) * kNormGroup * kNormIters;
 typedef float F4 __attribute__((ext_vector_type(4)));
 
-__global__ void norm_zero_kernel(NormBatch batch) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < batch.n_tensors) *batch.t[i].out = 0.0;
+// One wave per tensor: adds up the tensor's slots, writes the sum and leaves the slots zero for
+// the next launch.
+__global__ __launch_bounds__(kSumSlots) void norm_finish_kernel(NormBatch batch) {
+    static_assert(kSumSlots == 64, "one wave reads one tensor's slots");
+    double* slot = batch.partials + (int64_t(blockIdx.x) * kSumSlots + threadIdx.x) * kSumSlotDoubles + kNormSlotDouble;
+    double x = *slot;
+    *slot = 0.0;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_down(x, off, 64);
+    if (threadIdx.x == 0) *batch.t[blockIdx.x].out = x;
 }
 
 __device__ __forceinline__ double block_sum(double x, double* lds4) {
@@ -45,19 +62,19 @@ __device__ __forceinline__ double block_sum(double x, double* lds4) {
     return lds4[0] + lds4[1] + lds4[2] + lds4[3];       // meaningful in every thread
 }
 
-__global__ __launch_bounds__(kThreads) void norm_kernel(NormBatch batch) {
-    __shared__ double part[4];
+__global__ __launch_bounds__(kNormThreads) void norm_kernel(NormBatch batch) {
     int ti = 0;
     const int bid = blockIdx.x;
     for (int i = 1; i < batch.n_tensors; ++i)
         if (bid >= batch.t[i].block_start) ti = i;
     const NormTensor& T = batch.t[ti];
     const int64_t numel = T.numel;
-    const int64_t chunk = int64_t(bid - T.block_start) * kNormElemsPerBlock;
+    const int local_block = bid - T.block_start;
+    const int64_t chunk = int64_t(local_block) * kNormElemsPerBlock;
     double acc = 0.0;
 #pragma unroll
     for (int it = 0; it < kNormIters; ++it) {
-        const int64_t j = chunk + (int64_t(it) * kThreads + threadIdx.x) * kNormGroup;
+        const int64_t j = chunk + (int64_t(it) * kNormThreads + threadIdx.x) * kNormGroup;
         if (j + kNormGroup <= numel) {
             // streamed once: non-temporal accesses measured 5 % faster
             const F4 p = __builtin_nontemporal_load(reinterpret_cast<const F4*>(T.p + j));
@@ -76,8 +93,10 @@ __global__ __launch_bounds__(kThreads) void norm_kernel(NormBatch batch) {
             }
         }
     }
-    const double total = block_sum(acc, part);
-    if (threadIdx.x == 0) unsafeAtomicAdd(T.out, total);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+    if (threadIdx.x == 0)
+        unsafeAtomicAdd(batch.partials + (int64_t(ti) * kSumSlots + local_block % kSumSlots) * kSumSlotDoubles + kNormSlotDouble, acc);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -249,8 +268,9 @@ hipError_t launch_autofreeze_norms(hipStream_t stream, NormBatch& batch, int n_t
     batch.n_tensors = n_tensors;
     batch.update_snapshot = update_snapshot ? 1 : 0;
     if (n_tensors == 0 || batch.total_blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL(norm_zero_kernel, dim3(1), dim3(64), 0, stream, batch);
-    hipLaunchKernelGGL(norm_kernel, dim3(batch.total_blocks), dim3(kThreads), 0, stream, batch);
+    if (!batch.partials) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(norm_kernel, dim3(batch.total_blocks), dim3(kNormThreads), kNormResidencyLds, stream, batch);
+    hipLaunchKernelGGL(norm_finish_kernel, dim3(n_tensors), dim3(kSumSlots), 0, stream, batch);
     return hipGetLastError();
 }
 

@@ -726,6 +726,7 @@ int tf_autofreeze_norms(tf_ctx* ctx, void* hip_stream,
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int64_t epb = norm_elems_per_block();
     NormBatch batch;
+    batch.partials = ctx->ew_partials;
     int n = 0;
     int64_t blocks = 0;
     auto flush = [&]() -> hipError_t {

@@ -95,7 +95,7 @@ constexpr int kMaxTensorsPerLaunch = 32;
 // 6.8 million one-wave blocks of the 8B stage would queue up behind each other (measured: 82 ms
 // instead of 13).  The slots live in device memory owned by the context and are zero between launches.
 constexpr int kSumSlots = 64;
-constexpr int kSumSlotDoubles = 8;      // 64 bytes: {sum |E|, sum A, unused...}
+constexpr int kSumSlotDoubles = 8;      // 64 bytes: {sum |E|, sum A, sum of squares of the AutoFreeze pass, unused...}
 inline size_t ew_partials_bytes() { return size_t(kMaxTensorsPerLaunch) * kSumSlots * kSumSlotDoubles * sizeof(double); }
 
 struct EwBatch {            // passed by value as the kernel argument (< 4 KB)
@@ -130,6 +130,7 @@ struct NormTensor {
 };
 struct NormBatch {          // passed by value as the kernel argument
     NormTensor t[kMaxTensorsPerLaunch];
+    double* partials;       // the context's slots (device), shared with the optimizer's score sums; zero between launches
     int32_t n_tensors;
     int32_t total_blocks;
     int32_t update_snapshot;
