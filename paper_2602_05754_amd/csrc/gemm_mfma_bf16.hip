@@ -39,6 +39,7 @@
 #include "tf_internal.h"
 
 #include <type_traits>
+#include <utility>
 
 namespace tf {
 namespace {
@@ -71,6 +72,16 @@ typedef float F4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) bf16x4* LdsBf16x4Ptr;
 
 #define TF_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+// f(integral_constant<int, 0>), ..., f(integral_constant<int, N - 1>), in this order
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 // two binary32 -> packed bf16, round to nearest even (one v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
@@ -702,79 +713,65 @@ __global__ __launch_bounds__(kThreads) void gemm_mfma_kernel(GemmBatch batch) {
         const uint32_t deep_fill = lds_wave_base + d2;
         const uint32_t shallow_fill = lds_wave_base + s0;
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-        // Issue order below is pinned with scheduling fences.
+        // Issue order below is pinned with scheduling fences.  The 128 slots are instantiated with
+        // their numbers as compile-time constants (no loop to unroll, no index for the compiler to
+        // prove constant: every register array is addressed by literals).
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                if (u == 1 && i == 4) {
-                    // every operand read of this step's stages has been issued: wait for them and
-                    // for this wave's part of the next step (all loads but the eight issued at the
-                    // start of this step), then meet the other waves.  After the barrier the next
-                    // step's stages are complete and this step's may be overwritten.
-                    __builtin_amdgcn_s_waitcnt(0x0f78);     // vmcnt(8), other counters untouched
-                    __syncthreads();
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-#pragma unroll
-                for (int jj = 0; jj < 8; ++jj) {
-                    // boustrophedon over the tiles: consecutive MFMAs always share an operand
-                    const int j = (i & 1) ? 7 - jj : jj;
-                    // D rows <- n (B operand rows), D columns <- m: a lane then owns 4 consecutive n
-                    // of one output row m, i.e. 4 contiguous elements of row-major C.
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[u][j], fa[i],
-                                                                       (kFirst && u == 0) ? zero : acc[i][j], 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);          // the MFMA first, then what rides behind it
-                    // --- operand reads: this slot's read, from the address formed one slot ago; then
-                    // the address for the next slot's (the slot after the step's last one is the next
-                    // step's first, whose stages are this step's next ones) ---
-                    {
-                        const FragRead rd = frag_read_at(u, i, jj);
-                        if (rd.op == 1) fa[rd.idx] = read_frag<kTN>(frag_at, rd.u);
-                        if (rd.op == 2) fb[rd.u][rd.idx] = read_frag<kTN>(frag_at, rd.u);
-                        const int sl = (u * 64 + i * 8 + jj + 1) % 128;
-                        const bool wrap = u == 1 && i == 7 && jj == 7;
-                        const FragRead nx = frag_read_at(sl >> 6, (sl >> 3) & 7, sl & 7);
-                        if (nx.op != 0)
-                            frag_at = frag_address<kTN>(stage_lds[wrap ? 1 : nx.next][nx.op - 1],
-                                                        nx.op == 1 ? fr.a[nx.idx] : fr.b[nx.idx], nx.u);
-                    }
-                    // --- stage fills: one load after every fourth MFMA, the rate at which the
-                    // texture-address unit, which the waves share, takes them ---
-                    if (u == 0 && i < 4 && (jj == 2 || jj == 6)) {       // deep operand of the step after the next
-                        switch (2 * i + (jj >> 2)) {
-#define TF_FILL_CASE(Q) case Q: fill_load<Q>(deep(cur).g, deep(cur).g2, deep(cur).v, deep_fill); break;
-                            TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
-                            TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
-#undef TF_FILL_CASE
-                        }
-                    }
-                    // (the very last slot stays free for the loop's back edge)
-                    if (u == 1 && i >= 4 && (jj == 3 || jj == (i == 7 ? 6 : 7))) {   // its shallow operand, into the stage just freed
-                        switch (2 * (i - 4) + (jj >> 2)) {
-#define TF_FILL_CASE(Q) case Q: fill_load<Q>(lag.g, lag.g2, lag.v, shallow_fill); break;
-                            TF_FILL_CASE(0) TF_FILL_CASE(1) TF_FILL_CASE(2) TF_FILL_CASE(3)
-                            TF_FILL_CASE(4) TF_FILL_CASE(5) TF_FILL_CASE(6) TF_FILL_CASE(7)
-#undef TF_FILL_CASE
-                        }
-                    }
-                    // --- in between, the position moves on: pieces in the slots that hold nothing else ---
-                    if (u == 0 && i == 4 && jj == 1) keep_lag_s();
-                    if (u == 0 && i == 4 && jj == 2) keep_lag_v(0);
-                    if (u == 0 && i == 4 && jj == 3) keep_lag_v(1);
-                    if (u == 0 && i >= 5 && jj != 0 && jj != 4) {
-                        // rows 5, 6, 7: jj = 1, 2, 3, 5, 6, 7 -> pieces 0 .. 17
-                        const int n = 6 * (i - 5) + (jj < 4 ? jj - 1 : jj - 2);
-                        if (n < kAdvancePieces) advance_piece(n);
-                    }
-                    if (u == 1 && i == 0 && jj == 2) rotate_deep(0);     // the step itself works on copies taken at its top
-                    if (u == 1 && i == 0 && jj == 3) rotate_deep(1);
-                    if (u == 1 && i == 0 && jj == 5) rotate_shallow();
-                    __builtin_amdgcn_sched_barrier(0);
-                }
+        static_for<128>([&](auto slot_tag) __attribute__((always_inline)) {
+            constexpr int slot = decltype(slot_tag)::value;
+            constexpr int u = slot >> 6, i = (slot >> 3) & 7, jj = slot & 7;
+            if constexpr (u == 1 && i == 4 && jj == 0) {
+                // every operand read of this step's stages has been issued: wait for them and
+                // for this wave's part of the next step (all loads but the eight issued at the
+                // start of this step), then meet the other waves.  After the barrier the next
+                // step's stages are complete and this step's may be overwritten.
+                __builtin_amdgcn_s_waitcnt(0x0f78);     // vmcnt(8), other counters untouched
+                __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
             }
-        }
+            // boustrophedon over the tiles: consecutive MFMAs always share an operand
+            constexpr int j = (i & 1) ? 7 - jj : jj;
+            // D rows <- n (B operand rows), D columns <- m: a lane then owns 4 consecutive n
+            // of one output row m, i.e. 4 contiguous elements of row-major C.
+            if constexpr (kFirst && u == 0)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[u][j], fa[i], zero, 0, 0, 0);
+            else
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[u][j], fa[i], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);          // the MFMA first, then what rides behind it
+            // --- operand reads: this slot's read, from the address formed one slot ago; then
+            // the address for the next slot's (the slot after the step's last one is the next
+            // step's first, whose stages are this step's next ones) ---
+            {
+                constexpr FragRead rd = frag_read_at(u, i, jj);
+                if constexpr (rd.op == 1) fa[rd.idx] = read_frag<kTN>(frag_at, rd.u);
+                if constexpr (rd.op == 2) fb[rd.u][rd.idx] = read_frag<kTN>(frag_at, rd.u);
+                constexpr int sl = (slot + 1) % 128;
+                constexpr bool wrap = slot == 127;
+                constexpr FragRead nx = frag_read_at(sl >> 6, (sl >> 3) & 7, sl & 7);
+                if constexpr (nx.op == 1) frag_at = frag_address<kTN>(stage_lds[wrap ? 1 : nx.next][0], fr.a[nx.idx], nx.u);
+                if constexpr (nx.op == 2) frag_at = frag_address<kTN>(stage_lds[wrap ? 1 : nx.next][1], fr.b[nx.idx], nx.u);
+            }
+            // --- stage fills: one load after every fourth MFMA, the rate at which the
+            // texture-address unit, which the waves share, takes them ---
+            if constexpr (u == 0 && i < 4 && (jj == 2 || jj == 6))        // deep operand of the step after the next
+                fill_load<2 * i + (jj >> 2)>(deep(cur).g, deep(cur).g2, deep(cur).v, deep_fill);
+            // (the very last slot stays free for the loop's back edge)
+            if constexpr (u == 1 && i >= 4 && (jj == 3 || jj == (i == 7 ? 6 : 7)))   // its shallow operand, into the stage just freed
+                fill_load<2 * (i - 4) + (jj >> 2)>(lag.g, lag.g2, lag.v, shallow_fill);
+            // --- in between, the position moves on: pieces in the slots that hold nothing else ---
+            if constexpr (u == 0 && i == 4 && jj == 1) keep_lag_s();
+            if constexpr (u == 0 && i == 4 && jj == 2) keep_lag_v(0);
+            if constexpr (u == 0 && i == 4 && jj == 3) keep_lag_v(1);
+            if constexpr (u == 0 && i >= 5 && jj != 0 && jj != 4) {
+                // rows 5, 6, 7: jj = 1, 2, 3, 5, 6, 7 -> pieces 0 .. 17
+                constexpr int n = 6 * (i - 5) + (jj < 4 ? jj - 1 : jj - 2);
+                if constexpr (n < kAdvancePieces) advance_piece(n);
+            }
+            if constexpr (u == 1 && i == 0 && jj == 2) rotate_deep(0);     // the step itself works on copies taken at its top
+            if constexpr (u == 1 && i == 0 && jj == 3) rotate_deep(1);
+            if constexpr (u == 1 && i == 0 && jj == 5) rotate_shallow();
+            __builtin_amdgcn_sched_barrier(0);
+        });
     };
 
     // Tiles of this workgroup; the inner loop is the hot one.  When the fill position has
