@@ -55,6 +55,40 @@ def test_autofreeze_norms_and_snapshot(ctx, update):
         assert all(got2[i] == 0.0 for i in range(len(numel)) if not mask[i])
 
 
+def test_autofreeze_norms_with_more_tensors_than_one_launch_holds(ctx):
+    """75 tensors need three launches of the norm pass; the per-tensor sums are gathered through
+    slots that every launch must leave zero for the next one (also for the optimizer's score sums,
+    which share them).  Sizes from one element to many one-wave blocks per slot."""
+    rs = np.random.default_rng(260205754 + 77)
+    numel = [int(n) for n in rs.integers(1, 3000, size=72)] + [64 * 512 * 3 + 5, 700001, 2]
+    p = [_f32(rs.standard_normal(n) * 0.02) for n in numel]
+    snap = [_f32(a + rs.standard_normal(a.size) * 1e-4) for a in p]
+    mask = np.zeros(len(numel), np.uint8)
+    mask[[5, 40, 73]] = 1
+    dp = [torch.from_numpy(a).cuda() for a in p]
+    ds = [torch.from_numpy(a).cuda() for a in snap]
+    out = torch.full((len(numel),), -7.0, dtype=torch.float64, device="cuda")
+    for rep in range(2):            # the second call finds the slots as the first left them
+        tf.tf_autofreeze_norms(ctx, numel, dp, ds, out, tensor_freeze_mask=mask, update_snapshot=False)
+        got = out.cpu().numpy()
+        for i, n in enumerate(numel):
+            if mask[i]:
+                assert got[i] == -7.0
+            else:
+                assert got[i] == pytest.approx(oracle.autofreeze_sqnorm(p[i], snap[i]), rel=1e-12), (rep, i, n)
+    # the optimizer's score sums go through the same slots: still exact after the norm passes
+    n = 3000
+    E = _f32(rs.standard_normal(n) * 1e-5)
+    A = _f32(np.abs(rs.standard_normal(n)) * 1e-4)
+    d = _f32(rs.standard_normal(n) * 1e-5)
+    dE, dA, dd = (torch.from_numpy(x.copy()).cuda() for x in (E, A, d))
+    sums = torch.zeros(2, dtype=torch.float64, device="cuda")
+    tf.tf_stability_update(ctx, [n], [dd], [dE], [dA], 0.99, score_sums=sums)
+    E64, A64 = E.astype(np.float64), A.astype(np.float64)
+    oracle.stability_update(d.astype(np.float64), E64, A64, 0.99)
+    assert sums.cpu().numpy() == pytest.approx(np.array(oracle.score_sums(E64, A64)), rel=1e-5)
+
+
 def test_autofreeze_check_sequence_matches_the_oracle_rule(ctx):
     """Three checks of a 14-layer stage whose early layers move less and less: norms -> scores ->
     prefix selection, every step against the oracle."""
