@@ -143,6 +143,38 @@ int tf_stage_backward(tf_ctx* ctx, void* hip_stream,
                       int accumulate);
 
 /*
+ * One microbatch of a step in which every microbatch has its own freeze mask
+ * (App. D.1, update rule: Delta_t = (1/M) sum_m U_{t,m} (.) g_{t,m}, the sum running
+ * over the microbatches in which a parameter is not frozen).  As
+ * tf_stage_backward, but whether a weight gradient is added to dW_l or
+ * overwrites it is said layer by layer:
+ *
+ *   for every l:                                           dX_l = dY_l * W_l^T
+ *   freeze_mask[l]==0 and accumulate_mask[l]==0:           dW_l  = X_l^T * dY_l
+ *   freeze_mask[l]==0 and accumulate_mask[l]==1:           dW_l += X_l^T * dY_l
+ *   freeze_mask[l]==1:                                     dW_l untouched
+ *
+ *   accumulate_mask  host, n_layers bytes (0 or 1), required.  The caller sets
+ *                    entry l to 0 in the first microbatch of the step in which
+ *                    layer l is not frozen and to 1 afterwards: the accumulators
+ *                    then need no clearing between steps and the first product
+ *                    of a step is written without the old values being read.
+ *                    Entries of frozen layers are ignored.
+ *   dw_dtype         TF_F32 as soon as one unfrozen layer adds (TF_ERR_DTYPE
+ *                    otherwise).
+ * Everything else, errors included, as tf_stage_backward.  The layers that add
+ * and the layers that overwrite go to separate launches.
+ */
+int tf_stage_backward_microbatch(tf_ctx* ctx, void* hip_stream,
+                                 int32_t n_layers, const tf_shape* shapes,
+                                 int64_t T, tf_dtype io_dtype,
+                                 const void* const* W, const void* const* X, const void* const* dY,
+                                 const uint8_t* freeze_mask,
+                                 void* const* dX,
+                                 void* const* dW, tf_dtype dw_dtype,
+                                 const uint8_t* accumulate_mask);
+
+/*
  * Masked AdamW step over n_tensors tensors, optionally fused with the APF
  * stability recurrences (App. D.1 update rule with U = 1 - I; optimizer from
  * Table exp_setup; Sec. 2.3 for E, E^abs).  For every element j of tensor i that

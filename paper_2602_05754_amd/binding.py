@@ -24,6 +24,7 @@ EXPORTED_SYMBOLS = [
     "tf_autofreeze_norms", "tf_autofreeze_scores", "tf_autofreeze_select", "tf_reconcile_mask",
     "tf_reconcile_mask_static",
     "tf_stage_backward_blocks", "tf_stage_backward_shared", "tf_select_row_blocks", "tf_row_blocks_to_bits",
+    "tf_stage_backward_microbatch",
     "tf_pipeline_dag", "tf_dag_start_times", "tf_freeze_ratio_lp", "tf_actual_freeze_ratio",
 ]
 
@@ -75,6 +76,9 @@ def load_library():
     lib.tf_stage_backward.restype = ctypes.c_int
     lib.tf_stage_backward.argtypes = [vp, vp, i32, vp, i64, ctypes.c_int, vp, vp, vp, vp, vp, vp,
                                       ctypes.c_int, ctypes.c_int]
+    lib.tf_stage_backward_microbatch.restype = ctypes.c_int
+    lib.tf_stage_backward_microbatch.argtypes = [vp, vp, i32, vp, i64, ctypes.c_int, vp, vp, vp, vp, vp, vp,
+                                                 ctypes.c_int, vp]
     lib.tf_masked_adamw.restype = ctypes.c_int
     lib.tf_masked_adamw.argtypes = [vp, vp, i32, vp, vp, vp, vp, vp, ctypes.c_int, f32, vp, vp, vp, vp,
                                     f32, f32, f32, f32, f32, vp, vp, f32, vp]
@@ -362,6 +366,32 @@ def tf_stage_backward(ctx, shapes: Sequence[tuple], T: int, io_dtype: int,
                                L, sh.ctypes.data, int(T), int(io_dtype),
                                pW, pX, pdY, fm_p, pdX, pdW, int(dw_dtype), 1 if accumulate else 0)
     _raise(ctx, rc, "tf_stage_backward")
+
+
+def tf_stage_backward_microbatch(ctx, shapes: Sequence[tuple], T: int, io_dtype: int,
+                                 W, X, dY, freeze_mask, dX, dW, dw_dtype: int,
+                                 accumulate_mask, stream=None) -> None:
+    """tf_stage_backward with the choice between dW_l = and dW_l += made layer by layer
+    (accumulate_mask[l] = 0 / 1).  See include/tf.h."""
+    lib = load_library()
+    L = len(shapes)
+    sh = np.ascontiguousarray(np.asarray(shapes, dtype=np.int64).reshape(L, 2))
+    fm, fm_p = _host(freeze_mask, np.uint8, L)
+    am, am_p = _host(accumulate_mask, np.uint8, L)
+    _check_seq(W, sh[:, 0] * sh[:, 1], io_dtype, "W", ctx=ctx)
+    _check_seq(dY, T * sh[:, 1], io_dtype, "dY", ctx=ctx)
+    _check_seq(dX, T * sh[:, 0], io_dtype, "dX", ctx=ctx)
+    _check_seq(X, T * sh[:, 0], io_dtype, "X", fm, ctx=ctx)
+    _check_seq(dW, sh[:, 0] * sh[:, 1], dw_dtype, "dW", fm, ctx=ctx)
+    kW, pW = _ptr_array(W, L)
+    kX, pX = _ptr_array(X, L)
+    kdY, pdY = _ptr_array(dY, L)
+    kdX, pdX = _ptr_array(dX, L)
+    kdW, pdW = _ptr_array(dW, L)
+    rc = lib.tf_stage_backward_microbatch(_ctx_handle(ctx), _stream_handle(stream) if ctx is not None else None,
+                                          L, sh.ctypes.data, int(T), int(io_dtype),
+                                          pW, pX, pdY, fm_p, pdX, pdW, int(dw_dtype), am_p)
+    _raise(ctx, rc, "tf_stage_backward_microbatch")
 
 
 def tf_masked_adamw(ctx, numel: Sequence[int], p_master, m, v, grad, grad_dtype: int,

@@ -322,20 +322,30 @@ int tf_profile_collect(tf_ctx* ctx, int32_t capacity, int32_t* kinds, float* ms,
 
 int tf_last_hip_error(const tf_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
 
-int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
-                             int32_t n_layers, const tf_shape* shapes,
-                             int64_t T, tf_dtype io_dtype,
-                             const void* const* W, const void* const* X, const void* const* dY,
-                             const uint8_t* freeze_mask,
-                             const uint8_t* const* row_block_mask, int32_t block_rows,
-                             const int32_t* input_group,
-                             void* const* dX,
-                             void* const* dW, tf_dtype dw_dtype,
-                             int accumulate) {
+// The stage backward behind every entry point.  `accumulate_mask`, when given, says layer by
+// layer whether the weight gradient is added to dW_l (1) or overwrites it (0) and replaces
+// `accumulate`.
+static int stage_backward_impl(tf_ctx* ctx, void* hip_stream,
+                               int32_t n_layers, const tf_shape* shapes,
+                               int64_t T, tf_dtype io_dtype,
+                               const void* const* W, const void* const* X, const void* const* dY,
+                               const uint8_t* freeze_mask,
+                               const uint8_t* const* row_block_mask, int32_t block_rows,
+                               const int32_t* input_group,
+                               void* const* dX,
+                               void* const* dW, tf_dtype dw_dtype,
+                               int accumulate, const uint8_t* accumulate_mask) {
     // ---- validation: no HIP call before this block has passed ----
     if (n_layers < 0) return TF_ERR_INVALID_ARG;
     if (!valid_dtype(io_dtype) || !valid_dtype(dw_dtype)) return TF_ERR_DTYPE;
     if (accumulate != 0 && accumulate != 1) return TF_ERR_INVALID_ARG;
+    if (accumulate_mask) {
+        accumulate = 0;
+        for (int32_t l = 0; l < n_layers; ++l) {
+            if (accumulate_mask[l] > 1) return TF_ERR_INVALID_ARG;
+            if (accumulate_mask[l] && !(freeze_mask && freeze_mask[l] == 1)) accumulate = 1;
+        }
+    }
     if (accumulate && dw_dtype != TF_F32) return TF_ERR_DTYPE;
     if (io_dtype == TF_F32 && dw_dtype != TF_F32) return TF_ERR_DTYPE;
     if (row_block_mask && block_rows <= 0) return TF_ERR_INVALID_ARG;
@@ -448,13 +458,18 @@ int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
 
     // weight gradients: what is frozen - a layer, or a block of rows of one - is simply not
     // in the plan.
+    // Layers whose gradient is added to what dW_l holds and layers whose gradient overwrites it
+    // are two plans (two kernels: the adding one fetches the old values).
     plan.clear();
+    std::vector<Planned> plan_set, plan_add;
     for (int32_t l = 0; l < n_layers; ++l) {
         if (freeze_mask && freeze_mask[l]) continue;
+        const bool add = accumulate_mask ? accumulate_mask[l] != 0 : accumulate != 0;
+        std::vector<Planned>& dst = add ? plan_add : plan_set;
         const int64_t K = shapes[l].K, N = shapes[l].N;
         const uint8_t* rm = row_block_mask ? row_block_mask[l] : nullptr;
         if (!rm) {
-            plan.push_back(Planned{X[l], dY[l], dW[l], K, N, T, K, N, ~0ull, {}});
+            dst.push_back(Planned{X[l], dY[l], dW[l], K, N, T, K, N, ~0ull, {}});
             continue;
         }
         const int64_t nb = K / block_rows;
@@ -469,7 +484,7 @@ int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
             for (int64_t b = 0; b < nb; ++b)
                 if (!rm[b])
                     for (int64_t q = 0; q < per; ++q) { bits |= 1ull << (b * per + q); rows += tile; }
-            if (rows > 0) plan.push_back(Planned{X[l], dY[l], dW[l], rows, N, T, K, N, rows == K ? ~0ull : bits, {}});
+            if (rows > 0) dst.push_back(Planned{X[l], dY[l], dW[l], rows, N, T, K, N, rows == K ? ~0ull : bits, {}});
             continue;
         }
         // Otherwise each run of unfrozen row blocks is one problem: columns [k0, k1) of X
@@ -483,13 +498,42 @@ int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
                         static_cast<char*>(dW[l]) + k0 * N * dw_size, rows, N, T, K, N, ~0ull, {}};
             run.rows_before = k0;                    // columns of X on either side of the run's own
             run.rows_after = K - k0 - rows;
-            plan.push_back(run);
+            dst.push_back(run);
             b = e1;
         }
     }
-    e = launch_planned(ctx, stream, plan, Layout::kTN, in_dt, to_dtype(dw_dtype), accumulate != 0);
+    e = launch_planned(ctx, stream, plan_set, Layout::kTN, in_dt, to_dtype(dw_dtype), false);
+    if (e != hipSuccess) return hip_fail(ctx, e);
+    e = launch_planned(ctx, stream, plan_add, Layout::kTN, in_dt, to_dtype(dw_dtype), true);
     if (e != hipSuccess) return hip_fail(ctx, e);
     return TF_OK;
+}
+
+int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
+                             int32_t n_layers, const tf_shape* shapes,
+                             int64_t T, tf_dtype io_dtype,
+                             const void* const* W, const void* const* X, const void* const* dY,
+                             const uint8_t* freeze_mask,
+                             const uint8_t* const* row_block_mask, int32_t block_rows,
+                             const int32_t* input_group,
+                             void* const* dX,
+                             void* const* dW, tf_dtype dw_dtype,
+                             int accumulate) {
+    return stage_backward_impl(ctx, hip_stream, n_layers, shapes, T, io_dtype, W, X, dY, freeze_mask,
+                               row_block_mask, block_rows, input_group, dX, dW, dw_dtype, accumulate, nullptr);
+}
+
+int tf_stage_backward_microbatch(tf_ctx* ctx, void* hip_stream,
+                                 int32_t n_layers, const tf_shape* shapes,
+                                 int64_t T, tf_dtype io_dtype,
+                                 const void* const* W, const void* const* X, const void* const* dY,
+                                 const uint8_t* freeze_mask,
+                                 void* const* dX,
+                                 void* const* dW, tf_dtype dw_dtype,
+                                 const uint8_t* accumulate_mask) {
+    if (n_layers > 0 && !accumulate_mask) return TF_ERR_INVALID_ARG;
+    return stage_backward_impl(ctx, hip_stream, n_layers, shapes, T, io_dtype, W, X, dY, freeze_mask,
+                               nullptr, 0, nullptr, dX, dW, dw_dtype, 0, accumulate_mask);
 }
 
 int tf_stage_backward(tf_ctx* ctx, void* hip_stream,

@@ -90,6 +90,23 @@ def test_stage_backward_validation_precedes_any_gpu_work():
     assert shared([4 * A, 4 * A], [0, 1]) == ALIAS
 
 
+def test_stage_backward_microbatch_validation():
+    """The per-layer accumulate mask: required, 0 / 1 only, fp32 dW as soon as an unfrozen layer adds;
+    everything else is tf_stage_backward's validation."""
+    A = 4096
+    two = dict(shapes=[(8, 8), (8, 8)], W=[A, A], X=[2 * A, 2 * A], dY=[3 * A, 3 * A], dX=[4 * A, 6 * A], dW=[5 * A, 7 * A])
+    call = lambda fm, am, io=tf.TF_F32, dwt=tf.TF_F32, **kw: _code(
+        tf.tf_stage_backward_microbatch, None, two["shapes"], kw.get("T", 4), io, two["W"], kw.get("X", two["X"]), two["dY"],
+        fm, two["dX"], kw.get("dW", two["dW"]), dwt, am)
+    assert call([0, 0], [0, 1]) == -1                       # only the NULL ctx is left to complain about
+    assert call([0, 0], None) == -1 and call([0, 0], [0, 2]) == -1
+    assert call([0, 0], [0, 1], io=tf.TF_BF16, dwt=tf.TF_BF16) == -3        # an unfrozen layer adds: fp32 dW
+    assert call([0, 1], [0, 1], io=tf.TF_BF16, dwt=tf.TF_BF16, X=[2 * A, None], dW=[5 * A, None]) == -1   # the adding layer is frozen
+    assert call([0, 0], [0, 0], io=tf.TF_BF16, dwt=tf.TF_BF16) == -1
+    assert call([0, 0], [1, 1], T=0) == -2
+    assert call([0, 0], [1, 1], dW=[5 * A, 5 * A]) == -8    # aliasing outputs
+
+
 def test_tile_order_of_a_persistent_launch():
     """Every logical tile is visited once, and the tiles of one workgroup come in increasing
     order (the device-side search for a tile's problem only moves forward), for grids that are

@@ -133,6 +133,44 @@ def test_fp32_accumulation_over_microbatches_with_per_microbatch_masks(ctx, dims
             assert_elementwise(host64(gacc[l]), acc_o[l], "f32", f"acc[{l}]", scale=10.0)
 
 
+@pytest.mark.parametrize("dims", [dict(d=256, kv=256, ffn=512, T=256), dict(d=512, kv=256, ffn=768, T=320),
+                                  dict(d=136, kv=40, ffn=72, T=50)])
+def test_microbatches_where_a_layers_first_product_overwrites_its_accumulator(ctx, dims):
+    # The same sum over microbatches (App. D.1 update rule), with the choice between "=" and "+="
+    # made layer by layer: a layer's first unfrozen microbatch of the step overwrites whatever its
+    # accumulator holds (here: NaN canaries, which an addition would keep), later ones add.
+    cfg = wl.scaled(wl.CONFIGS[5], blocks=1, microbatches=4, **dims)
+    sh = cfg.shapes; T = cfg.T; L = cfg.n_layers
+    ratios = [0.6, 0.2, 0.8, 0.4]
+    masks = [wl.permutation_mask(cfg, ratios[m], microbatch=m) for m in range(4)]
+    for mk in masks:
+        mk[5] = 1                            # one layer stays frozen in every microbatch
+    always = np.minimum.reduce(masks)
+    assert always.sum() == 1 and (masks[0] & (1 - masks[1])).sum() >= 1     # ... and some layers start late
+    acc_o = [np.zeros((k, n)) for k, n in sh]
+    gacc = [canary((k, n), torch.float32) for k, n in sh]
+    before = [raw_bytes(t) for t in gacc]
+    seen = np.zeros(L, np.uint8)             # the layer has been unfrozen in an earlier microbatch
+    for m in range(4):
+        W, X, dY = _inputs(cfg, T, microbatch=m)
+        dXo, _ = _oracle_backward(cfg, T, W, X, dY, masks[m], dW0=acc_o, accumulate=True)
+        gdX = [torch.empty((T, k), dtype=torch.bfloat16, device="cuda") for k, n in sh]
+        tf.tf_stage_backward_microbatch(ctx, sh, T, tf.TF_BF16, [dev(w, "bf16") for w in W], [dev(x, "bf16") for x in X],
+                                        [dev(d, "bf16") for d in dY], masks[m], gdX, gacc, tf.TF_F32, seen.copy())
+        torch.cuda.synchronize()
+        seen |= (1 - masks[m]).astype(np.uint8)
+        for l in range(L):
+            assert rel_fro(host64(gdX[l]), dXo[l]) <= TOL["bf16"]
+            assert_elementwise(host64(gdX[l]), dXo[l], "bf16", f"dX[{l}] microbatch {m}")
+    for l in range(L):
+        if always[l]:
+            assert raw_bytes(gacc[l]) == before[l]
+        else:
+            e = rel_fro(host64(gacc[l]), acc_o[l])
+            assert e <= 1e-5 * 10, f"acc[{l}] rel_fro {e:.3e}"
+            assert_elementwise(host64(gacc[l]), acc_o[l], "f32", f"acc[{l}]", scale=10.0)
+
+
 def test_degenerate_calls(ctx):
     tf.tf_stage_backward(ctx, [], 16, tf.TF_BF16, [], [], [], [], [], [], tf.TF_BF16)      # no layers
     # all frozen, X and dW absent altogether
