@@ -618,33 +618,56 @@ def bench_microbatches(args, cfg, ctx, wl, tf, torch, st=None):
         dY = tf.PtrTable([st.dY[l][:T] for l in range(st.L)])
     L, P = st.L, cfg.n_params
     dX = tf.PtrTable([st.dX[l][:T] for l in range(L)])
-    acc = tf.PtrTable([torch.zeros((k, n), device="cuda") for k, n in st.shapes])
+    acc_t = [torch.zeros((k, n), device="cuda") for k, n in st.shapes]
+    acc = tf.PtrTable(acc_t)
     ratios = wl.microbatch_ratios(cfg)
     masks = [wl.permutation_mask(cfg, r, microbatch=i) for i, r in enumerate(ratios)]
+    # a layer's first unfrozen microbatch of the step overwrites its accumulator, the later ones add
+    adds, seen = [], np.zeros(L, np.uint8)
+    for mk in masks:
+        adds.append(seen.copy())
+        seen |= (1 - mk).astype(np.uint8)
     def one_step():
+        for mk, am in zip(masks, adds):
+            tf.tf_stage_backward_microbatch(ctx, st.shapes, T, tf.TF_BF16, st.W, X, dY, mk, dX, acc, tf.TF_F32, am)
+    def one_step_all_adding():      # one flag per call: every call adds, so the step starts by clearing the accumulators
+        for l in range(L):
+            if seen[l]:
+                acc_t[l].zero_()
         for mk in masks:
             tf.tf_stage_backward(ctx, st.shapes, T, tf.TF_BF16, st.W, X, dY, mk, dX, acc, tf.TF_F32, accumulate=True)
+    dt_add, _ = _timed(ctx, torch, one_step_all_adding, args.steps, args.warmup)
     dt, prof = _timed(ctx, torch, one_step, args.steps, args.warmup)
-    dx = [t for k, t in prof if k == "dx_mfma"]; dw = [t for k, t in prof if k == "dw_mfma"]
+    # per call: one dX launch, then one or two dW launches (the overwriting layers, the adding layers)
+    calls = []
+    for k, t in prof:
+        if k == "dx_mfma":
+            calls.append([t, 0.0])
+        elif k == "dw_mfma" and calls:
+            calls[-1][1] += t
     per_call = []
-    for i, (r, mk) in enumerate(zip(ratios, masks)):
+    for i, (r, mk, am) in enumerate(zip(ratios, masks, adds)):
         phi = wl.frozen_param_fraction(cfg, mk)
-        tdx = float(np.mean(dx[i::len(masks)])); tdw = float(np.mean(dw[i::len(masks)]))
-        # minimum traffic of the accumulating dW launch: X and dY read once, the fp32 gradient read and written
-        unfrozen_bytes = (1 - phi) * P * 8 + 2 * T * sum((k + n) * (0 if mk[l] else 1) for l, (k, n) in enumerate(st.shapes))
+        tdx = float(np.mean([c[0] for c in calls[i::len(masks)]])); tdw = float(np.mean([c[1] for c in calls[i::len(masks)]]))
+        # minimum traffic of the dW launches: X and dY read once, the fp32 gradient written, and read where it is added to
+        grad_bytes = sum(k * n * (8 if am[l] else 4) for l, (k, n) in enumerate(st.shapes) if not mk[l])
+        unfrozen_bytes = grad_bytes + 2 * T * sum((k + n) * (0 if mk[l] else 1) for l, (k, n) in enumerate(st.shapes))
         dw_flop = 2.0 * T * P * (1 - phi)
         t_roof_ms = max(dw_flop / (PEAK_BF16_TFLOPS * 1e12), unfrozen_bytes / (PEAK_HBM_GBPS * 1e9)) * 1e3
-        per_call.append({"r": r, "n_frozen": int(mk.sum()), "phi": phi, "dx_ms": tdx, "dw_ms": tdw,
+        per_call.append({"r": r, "n_frozen": int(mk.sum()), "phi": phi, "layers_overwriting": int(((1 - mk) * (1 - am)).sum()),
+                         "dx_ms": tdx, "dw_ms": tdw,
                          "dx_tflops": 2.0 * T * P / tdx / 1e9, "dw_tflops": dw_flop / tdw / 1e9,
                          "dw_GBps_min_traffic": unfrozen_bytes / tdw / 1e6, "dw_frac_of_its_roof": t_roof_ms / tdw})
         log(f"cfg5 call {i}: r={r} phi={phi:.3f} dX {tdx:.3f} ms ({per_call[-1]['dx_tflops']:.0f} TFLOP/s), "
             f"dW {tdw:.3f} ms ({per_call[-1]['dw_tflops']:.0f} TFLOP/s, {per_call[-1]['dw_GBps_min_traffic']:.0f} GB/s of its minimum traffic, "
-            f"{100 * per_call[-1]['dw_frac_of_its_roof']:.0f} % of max(MFMA, HBM) roof)")
+            f"{100 * per_call[-1]['dw_frac_of_its_roof']:.0f} % of max(MFMA, HBM) roof; {per_call[-1]['layers_overwriting']} layers overwrite)")
+    log(f"cfg5: {dt * 1e3:.2f} ms per 8 calls ({dt_add * 1e3:.2f} ms with one flag per call: the accumulators cleared, then every call adding)")
     tot_bytes = sum(c["dw_GBps_min_traffic"] * c["dw_ms"] * 1e6 for c in per_call)
     tot_ms = sum(c["dw_ms"] for c in per_call)
     return {"workload": f"cfg5 {cfg.name}: 8 calls of T={T}, fp32 dW accumulation, {L} tensors, P={P} params",
             "ms_per_8_calls": dt * 1e3, "tokens_per_s": 8 * T / dt, "calls": per_call,
-            "roofline_dw": {"kernel": "gemm_mfma_kernel<TN, fp32 read-modify-write> (dW += X^T dY, unfrozen layers only), mean over the 8 calls",
+            "ms_per_8_calls_cleared_then_every_call_adding": dt_add * 1e3,
+            "roofline_dw": {"kernel": "gemm_mfma_kernel<TN, fp32 out> (dW = / += X^T dY per layer, unfrozen layers only), mean over the 8 calls",
                             "bound": "hbm", "achieved": tot_bytes / tot_ms / 1e6, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                             "frac": tot_bytes / tot_ms / 1e6 / PEAK_HBM_GBPS, "traffic": read_traffic("dw_mfma", 5),
                             "traffic_source": TRAFFIC_NOTE, "avg_launch_ms": tot_ms / len(per_call),

@@ -172,9 +172,12 @@ def test_operands_and_outputs_that_cross_a_4gib_address_boundary(ctx):
     del pool
 
 
-def test_llama8b_microbatch_accumulation_then_masked_update(ctx):
+@pytest.mark.parametrize("per_layer", [False, True])
+def test_llama8b_microbatch_accumulation_then_masked_update(ctx, per_layer):
     # BASELINE configs[4]: 8 sequential calls of 1024 tokens accumulating dW in fp32 for unfrozen
     # tensors only, a different ratio per call; then one optimizer step with grad_scale = 1/M.
+    # per_layer: through tf_stage_backward_microbatch, as bench.py times it - nothing is cleared, a
+    # layer's first unfrozen microbatch overwrites the canaries its accumulator starts with.
     cfg = wl.scaled(wl.CONFIGS[5], blocks=1)
     sh, T, L, M = cfg.shapes, cfg.T, cfg.n_layers, cfg.microbatches
     ratios = wl.microbatch_ratios(cfg)
@@ -183,7 +186,9 @@ def test_llama8b_microbatch_accumulation_then_masked_update(ctx):
     all_frozen = np.minimum.reduce(masks)
     W = [wl.gen_layer(cfg, l, T=8)[0] for l in range(L)]          # weights do not change between microbatches
     gW = [dev(w, "bf16") for w in W]
-    acc = [canary((k, n), torch.float32) if all_frozen[l] else torch.zeros((k, n), device="cuda") for l, (k, n) in enumerate(sh)]
+    acc = [canary((k, n), torch.float32) if all_frozen[l] or per_layer else torch.zeros((k, n), device="cuda")
+           for l, (k, n) in enumerate(sh)]
+    seen = np.zeros(L, np.uint8)
     before = [t.clone() for t in acc]
     rs = np.random.default_rng(23)
     samples = [_tile_samples(rs, k, n, per_tile=1) for k, n in sh]
@@ -193,7 +198,11 @@ def test_llama8b_microbatch_accumulation_then_masked_update(ctx):
         gX = [dev(h[1], "bf16") for h in host]
         gdY = [dev(h[2], "bf16") for h in host]
         gdX = [torch.empty((T, k), dtype=torch.bfloat16, device="cuda") for k, n in sh]
-        tf.tf_stage_backward(ctx, sh, T, tf.TF_BF16, gW, gX, gdY, masks[m], gdX, acc, tf.TF_F32, accumulate=True)
+        if per_layer:
+            tf.tf_stage_backward_microbatch(ctx, sh, T, tf.TF_BF16, gW, gX, gdY, masks[m], gdX, acc, tf.TF_F32, seen.copy())
+            seen |= (1 - masks[m]).astype(np.uint8)
+        else:
+            tf.tf_stage_backward(ctx, sh, T, tf.TF_BF16, gW, gX, gdY, masks[m], gdX, acc, tf.TF_F32, accumulate=True)
         torch.cuda.synchronize()
         for l in range(L):
             if not masks[m][l]:
