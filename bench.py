@@ -671,7 +671,10 @@ def bench_microbatches(args, cfg, ctx, wl, tf, torch, st=None):
                             "bound": "hbm", "achieved": tot_bytes / tot_ms / 1e6, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
                             "frac": tot_bytes / tot_ms / 1e6 / PEAK_HBM_GBPS, "traffic": read_traffic("dw_mfma", 5),
                             "traffic_source": TRAFFIC_NOTE, "avg_launch_ms": tot_ms / len(per_call),
-                            "frac_of_max_mfma_hbm_roof": float(np.mean([c["dw_frac_of_its_roof"] for c in per_call]))},
+                            "frac_of_max_mfma_hbm_roof": float(np.mean([c["dw_frac_of_its_roof"] for c in per_call])),
+                            # the calls in which every unfrozen layer adds (read-modify-write only: HBM is their roof)
+                            "frac_of_max_mfma_hbm_roof_calls_that_only_add": float(np.mean(
+                                [c["dw_frac_of_its_roof"] for c in per_call if c["layers_overwriting"] == 0] or [0.0]))},
             "roofline_dx": {"kernel": "gemm_mfma_kernel<NT> at T=1024", "bound": "mfma",
                             "achieved": float(np.mean([c["dx_tflops"] for c in per_call])), "peak": PEAK_BF16_TFLOPS,
                             "unit": "TFLOP/s", "frac": float(np.mean([c["dx_tflops"] for c in per_call])) / PEAK_BF16_TFLOPS,
