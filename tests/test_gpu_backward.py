@@ -171,6 +171,29 @@ def test_microbatches_where_a_layers_first_product_overwrites_its_accumulator(ct
             assert_elementwise(host64(gacc[l]), acc_o[l], "f32", f"acc[{l}]", scale=10.0)
 
 
+def test_microbatch_entry_point_with_nothing_to_add_equals_the_plain_backward(ctx):
+    # all accumulate_mask entries 0: the same launches as tf_stage_backward(accumulate = 0), bf16 dW allowed
+    cfg = wl.scaled(wl.CONFIGS[2], blocks=1, d=512, kv=256, ffn=768, T=512)
+    sh, T, L = cfg.shapes, cfg.T, cfg.n_layers
+    mask = wl.permutation_mask(cfg, 0.3)
+    W, X, dY = _inputs(cfg, T)
+    gW = [dev(w, "bf16") for w in W]; gX = [dev(x, "bf16") for x in X]; gdY = [dev(d, "bf16") for d in dY]
+    out = []
+    for entry in ("plain", "microbatch"):
+        gdX = [canary((T, k), torch.bfloat16) for k, n in sh]
+        gdW = [canary((k, n), torch.bfloat16) for k, n in sh]
+        if entry == "plain":
+            tf.tf_stage_backward(ctx, sh, T, tf.TF_BF16, gW, gX, gdY, mask, gdX, gdW, tf.TF_BF16)
+        else:
+            tf.tf_stage_backward_microbatch(ctx, sh, T, tf.TF_BF16, gW, gX, gdY, mask, gdX, gdW, tf.TF_BF16, np.zeros(L, np.uint8))
+        torch.cuda.synchronize()
+        out.append([raw_bytes(t) for t in gdX + gdW])
+    assert out[0] == out[1]
+    with pytest.raises(tf.TfError) as err:       # an unfrozen layer that adds needs fp32 accumulators
+        tf.tf_stage_backward_microbatch(ctx, sh, T, tf.TF_BF16, gW, gX, gdY, mask, gdX, gdW, tf.TF_BF16, 1 - mask)
+    assert err.value.code == -3
+
+
 def test_degenerate_calls(ctx):
     tf.tf_stage_backward(ctx, [], 16, tf.TF_BF16, [], [], [], [], [], [], tf.TF_BF16)      # no layers
     # all frozen, X and dW absent altogether
