@@ -623,10 +623,8 @@ def bench_microbatches(args, cfg, ctx, wl, tf, torch, st=None):
     ratios = wl.microbatch_ratios(cfg)
     masks = [wl.permutation_mask(cfg, r, microbatch=i) for i, r in enumerate(ratios)]
     # a layer's first unfrozen microbatch of the step overwrites its accumulator, the later ones add
-    adds, seen = [], np.zeros(L, np.uint8)
-    for mk in masks:
-        adds.append(seen.copy())
-        seen |= (1 - mk).astype(np.uint8)
+    adds, never = tf.tf_microbatch_plan(np.stack(masks))
+    seen = 1 - never                        # unfrozen in at least one microbatch: these accumulators are live
     def one_step():
         for mk, am in zip(masks, adds):
             tf.tf_stage_backward_microbatch(ctx, st.shapes, T, tf.TF_BF16, st.W, X, dY, mk, dX, acc, tf.TF_F32, am)

@@ -175,6 +175,20 @@ int tf_stage_backward_microbatch(tf_ctx* ctx, void* hip_stream,
                                  const uint8_t* accumulate_mask);
 
 /*
+ * Host-only bookkeeping for such a step (App. D.1, update rule).  freeze_masks
+ * is host memory, n_microbatches rows of n_layers bytes (row m = the mask of
+ * microbatch m, 1 = frozen).  Outputs, host memory:
+ *   accumulate_masks  n_microbatches x n_layers: the accumulate_mask of call m
+ *                     (1 where layer l was unfrozen in an earlier microbatch);
+ *   step_freeze_mask  n_layers: 1 where layer l was frozen in EVERY microbatch -
+ *                     the tensor_freeze_mask of the step's tf_masked_adamw call
+ *                     (its grad_scale is 1 / n_microbatches whatever the masks).
+ * TF_ERR_INVALID_ARG for NULL pointers, negative sizes or mask bytes above 1.
+ */
+int tf_microbatch_plan(int32_t n_microbatches, int32_t n_layers, const uint8_t* freeze_masks,
+                       uint8_t* accumulate_masks, uint8_t* step_freeze_mask);
+
+/*
  * Masked AdamW step over n_tensors tensors, optionally fused with the APF
  * stability recurrences (App. D.1 update rule with U = 1 - I; optimizer from
  * Table exp_setup; Sec. 2.3 for E, E^abs).  For every element j of tensor i that

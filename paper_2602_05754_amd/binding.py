@@ -24,7 +24,7 @@ EXPORTED_SYMBOLS = [
     "tf_autofreeze_norms", "tf_autofreeze_scores", "tf_autofreeze_select", "tf_reconcile_mask",
     "tf_reconcile_mask_static",
     "tf_stage_backward_blocks", "tf_stage_backward_shared", "tf_select_row_blocks", "tf_row_blocks_to_bits",
-    "tf_stage_backward_microbatch",
+    "tf_stage_backward_microbatch", "tf_microbatch_plan",
     "tf_pipeline_dag", "tf_dag_start_times", "tf_freeze_ratio_lp", "tf_actual_freeze_ratio",
 ]
 
@@ -88,6 +88,8 @@ def load_library():
     lib.tf_stability_scores.argtypes = [vp, i32, vp]
     lib.tf_select_lowest.restype = ctypes.c_int
     lib.tf_select_lowest.argtypes = [vp, i32, i32, vp]
+    lib.tf_microbatch_plan.restype = ctypes.c_int
+    lib.tf_microbatch_plan.argtypes = [i32, i32, vp, vp, vp]
     lib.tf_num_frozen.restype = i32
     lib.tf_num_frozen.argtypes = [f64, i32]
     lib.tf_profile_enable.restype = ctypes.c_int
@@ -470,6 +472,20 @@ def tf_select_lowest(scores, n_freeze: int) -> np.ndarray:
     rc = lib.tf_select_lowest(s.ctypes.data, s.size, int(n_freeze), out.ctypes.data)
     _raise(None, rc, "tf_select_lowest")
     return out[: s.size]
+
+
+def tf_microbatch_plan(freeze_masks):
+    """(accumulate_masks [M x L], step_freeze_mask [L]) of a step whose microbatch m has the freeze
+    mask freeze_masks[m].  See include/tf.h."""
+    fm = np.ascontiguousarray(np.asarray(freeze_masks, dtype=np.uint8))
+    if fm.ndim != 2:
+        raise ValueError("freeze_masks: one row per microbatch")
+    M, L = fm.shape
+    acc = np.zeros((M, L), dtype=np.uint8)
+    step = np.zeros(L, dtype=np.uint8)
+    rc = load_library().tf_microbatch_plan(M, L, fm.ctypes.data, acc.ctypes.data, step.ctypes.data)
+    _raise(None, rc, "tf_microbatch_plan")
+    return acc, step
 
 
 def tf_num_frozen(r: float, n: int) -> int:

@@ -739,6 +739,24 @@ int tf_select_lowest(const double* scores, int32_t n, int32_t n_freeze, uint8_t*
     return TF_OK;
 }
 
+int tf_microbatch_plan(int32_t n_microbatches, int32_t n_layers, const uint8_t* freeze_masks,
+                       uint8_t* accumulate_masks, uint8_t* step_freeze_mask) {
+    if (n_microbatches < 0 || n_layers < 0) return TF_ERR_INVALID_ARG;
+    if (n_layers == 0) return TF_OK;
+    if (!step_freeze_mask || (n_microbatches > 0 && (!freeze_masks || !accumulate_masks))) return TF_ERR_INVALID_ARG;
+    for (int64_t i = 0; i < int64_t(n_microbatches) * n_layers; ++i)
+        if (freeze_masks[i] > 1) return TF_ERR_INVALID_ARG;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        uint8_t seen = 0;                       // unfrozen in an earlier microbatch
+        for (int32_t m = 0; m < n_microbatches; ++m) {
+            accumulate_masks[int64_t(m) * n_layers + l] = seen;
+            if (!freeze_masks[int64_t(m) * n_layers + l]) seen = 1;
+        }
+        step_freeze_mask[l] = seen ? 0 : 1;
+    }
+    return TF_OK;
+}
+
 int32_t tf_num_frozen(double r, int32_t n) {
     if (n <= 0 || !(r > 0.0)) return 0;
     const double x = std::ceil(r * double(n) - 1e-9);

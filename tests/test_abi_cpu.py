@@ -107,6 +107,27 @@ def test_stage_backward_microbatch_validation():
     assert call([0, 0], [1, 1], dW=[5 * A, 5 * A]) == -8    # aliasing outputs
 
 
+def test_microbatch_plan_against_its_definition():
+    """accumulate_masks[m][l] = layer l was unfrozen in some microbatch before m; step_freeze_mask[l] =
+    frozen in every microbatch (App. D.1: the update sums over the microbatches that are not frozen)."""
+    rng = np.random.default_rng(5)
+    for M, L, p in [(1, 1, 0.5), (8, 56, 0.5), (3, 7, 0.9), (5, 4, 0.0), (4, 9, 1.0)]:
+        fm = (rng.random((M, L)) < p).astype(np.uint8)
+        acc, step = tf.tf_microbatch_plan(fm)
+        for l in range(L):
+            for m in range(M):
+                assert acc[m, l] == int(any(fm[q, l] == 0 for q in range(m)))
+            assert step[l] == int(all(fm[m, l] == 1 for m in range(M)))
+    # each unfrozen (m, l) is either the layer's first (overwrites) or a later one (adds): exactly one first per live layer
+    fm = (rng.random((8, 56)) < 0.6).astype(np.uint8)
+    acc, step = tf.tf_microbatch_plan(fm)
+    firsts = ((1 - fm) * (1 - acc)).sum(axis=0)
+    assert np.array_equal(firsts, 1 - step)
+    assert _code(tf.tf_microbatch_plan, np.full((2, 3), 2, np.uint8)) == -1
+    acc, step = tf.tf_microbatch_plan(np.zeros((0, 4), np.uint8))      # no microbatch: nothing was ever unfrozen
+    assert acc.shape == (0, 4) and step.tolist() == [1, 1, 1, 1]
+
+
 def test_tile_order_of_a_persistent_launch():
     """Every logical tile is visited once, and the tiles of one workgroup come in increasing
     order (the device-side search for a tile's problem only moves forward), for grids that are

@@ -188,7 +188,8 @@ def test_llama8b_microbatch_accumulation_then_masked_update(ctx, per_layer):
     gW = [dev(w, "bf16") for w in W]
     acc = [canary((k, n), torch.float32) if all_frozen[l] or per_layer else torch.zeros((k, n), device="cuda")
            for l, (k, n) in enumerate(sh)]
-    seen = np.zeros(L, np.uint8)
+    adds, never = tf.tf_microbatch_plan(np.stack(masks))
+    assert np.array_equal(never, all_frozen)
     before = [t.clone() for t in acc]
     rs = np.random.default_rng(23)
     samples = [_tile_samples(rs, k, n, per_tile=1) for k, n in sh]
@@ -199,8 +200,7 @@ def test_llama8b_microbatch_accumulation_then_masked_update(ctx, per_layer):
         gdY = [dev(h[2], "bf16") for h in host]
         gdX = [torch.empty((T, k), dtype=torch.bfloat16, device="cuda") for k, n in sh]
         if per_layer:
-            tf.tf_stage_backward_microbatch(ctx, sh, T, tf.TF_BF16, gW, gX, gdY, masks[m], gdX, acc, tf.TF_F32, seen.copy())
-            seen |= (1 - masks[m]).astype(np.uint8)
+            tf.tf_stage_backward_microbatch(ctx, sh, T, tf.TF_BF16, gW, gX, gdY, masks[m], gdX, acc, tf.TF_F32, adds[m])
         else:
             tf.tf_stage_backward(ctx, sh, T, tf.TF_BF16, gW, gX, gdY, masks[m], gdX, acc, tf.TF_F32, accumulate=True)
         torch.cuda.synchronize()
