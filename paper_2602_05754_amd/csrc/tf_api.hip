@@ -221,120 +221,19 @@ int validate_elementwise_common(int32_t n_tensors, const int64_t* numel,
     return TF_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-const char* tf_version(void) { return "0.1.0"; }
-
-const char* tf_strerror(int code) {
-    switch (code) {
-        case TF_OK: return "ok";
-        case TF_ERR_INVALID_ARG: return "invalid argument";
-        case TF_ERR_SHAPE: return "invalid shape or size";
-        case TF_ERR_DTYPE: return "unsupported dtype or dtype combination";
-        case TF_ERR_ALIGN: return "device pointer is not 16-byte aligned";
-        case TF_ERR_WORKSPACE: return "workspace allocation failed";
-        case TF_ERR_HIP: return "HIP runtime error (see tf_last_hip_error)";
-        case TF_ERR_NO_DEVICE: return "no usable gfx950 device";
-        case TF_ERR_ALIAS: return "an output buffer overlaps an input or another output";
-        default: return "unknown status code";
-    }
-}
-
-int tf_create(tf_ctx** out, int device_id) {
-    if (!out || device_id < 0) return TF_ERR_INVALID_ARG;
-    *out = nullptr;
-    int count = 0;
-    if (hipGetDeviceCount(&count) != hipSuccess || device_id >= count) return TF_ERR_NO_DEVICE;
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) return TF_ERR_NO_DEVICE;
-    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return TF_ERR_NO_DEVICE;
-    if (hipSetDevice(device_id) != hipSuccess) return TF_ERR_NO_DEVICE;
-    tf_ctx* ctx = new (std::nothrow) tf_ctx;
-    if (!ctx) return TF_ERR_WORKSPACE;
-    ctx->device_id = device_id;
-    ctx->last_hip_error = 0;
-    ctx->profiling = false;
-    ctx->rc_state = nullptr;
-    ctx->rc_state_static = nullptr;
-    ctx->lowp_is_rounded_master = false;
-    ctx->ew_partials = nullptr;
-    if (hipMalloc(reinterpret_cast<void**>(&ctx->rc_state), tf::rc_state_bytes()) != hipSuccess) {
-        delete ctx;
-        return TF_ERR_WORKSPACE;
-    }
-    void* st = nullptr;
-    if (static_scratch_address(device_id, &st) != hipSuccess ||      // device_id is current here
-        hipMalloc(reinterpret_cast<void**>(&ctx->ew_partials), tf::ew_partials_bytes()) != hipSuccess ||
-        hipMemset(ctx->ew_partials, 0, tf::ew_partials_bytes()) != hipSuccess) {
-        if (ctx->ew_partials) (void)hipFree(ctx->ew_partials);
-        (void)hipFree(ctx->rc_state);
-        delete ctx;
-        return TF_ERR_WORKSPACE;
-    }
-    ctx->rc_state_static = static_cast<tf::RcState*>(st);
-    *out = ctx;
-    return TF_OK;
-}
-
-int tf_destroy(tf_ctx* ctx) {
-    if (!ctx) return TF_ERR_INVALID_ARG;
-    for (tf_prof_rec& r : ctx->recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
-    for (hipEvent_t e : ctx->pool) (void)hipEventDestroy(e);
-    if (ctx->rc_state) (void)hipFree(ctx->rc_state);
-    if (ctx->ew_partials) (void)hipFree(ctx->ew_partials);
-    delete ctx;
-    return TF_OK;
-}
-
-int tf_assume_lowp_is_rounded_master(tf_ctx* ctx, int on) {
-    if (!ctx || (on != 0 && on != 1)) return TF_ERR_INVALID_ARG;
-    ctx->lowp_is_rounded_master = on != 0;
-    return TF_OK;
-}
-
-int tf_profile_enable(tf_ctx* ctx, int enable) {
-    if (!ctx || (enable != 0 && enable != 1)) return TF_ERR_INVALID_ARG;
-    ctx->profiling = enable != 0;
-    return TF_OK;
-}
-
-int tf_profile_collect(tf_ctx* ctx, int32_t capacity, int32_t* kinds, float* ms, int32_t* n_out) {
-    if (!ctx || !n_out || capacity < 0 || (capacity > 0 && (!kinds || !ms))) return TF_ERR_INVALID_ARG;
-    int32_t n = 0;
-    int rc = TF_OK;
-    for (tf_prof_rec& r : ctx->recs) {
-        if (n < capacity && rc == TF_OK) {
-            hipError_t e = hipEventSynchronize(r.stop);
-            float t = 0.f;
-            if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
-            if (e != hipSuccess) rc = hip_fail(ctx, e);
-            else { kinds[n] = r.kind; ms[n] = t; ++n; }
-        }
-        ctx->pool.push_back(r.start);
-        ctx->pool.push_back(r.stop);
-    }
-    ctx->recs.clear();
-    *n_out = n;
-    return rc;
-}
-
-int tf_last_hip_error(const tf_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
-
 // The stage backward behind every entry point.  `accumulate_mask`, when given, says layer by
 // layer whether the weight gradient is added to dW_l (1) or overwrites it (0) and replaces
 // `accumulate`.
-static int stage_backward_impl(tf_ctx* ctx, void* hip_stream,
-                               int32_t n_layers, const tf_shape* shapes,
-                               int64_t T, tf_dtype io_dtype,
-                               const void* const* W, const void* const* X, const void* const* dY,
-                               const uint8_t* freeze_mask,
-                               const uint8_t* const* row_block_mask, int32_t block_rows,
-                               const int32_t* input_group,
-                               void* const* dX,
-                               void* const* dW, tf_dtype dw_dtype,
-                               int accumulate, const uint8_t* accumulate_mask) {
+int stage_backward_impl(tf_ctx* ctx, void* hip_stream,
+                        int32_t n_layers, const tf_shape* shapes,
+                        int64_t T, tf_dtype io_dtype,
+                        const void* const* W, const void* const* X, const void* const* dY,
+                        const uint8_t* freeze_mask,
+                        const uint8_t* const* row_block_mask, int32_t block_rows,
+                        const int32_t* input_group,
+                        void* const* dX,
+                        void* const* dW, tf_dtype dw_dtype,
+                        int accumulate, const uint8_t* accumulate_mask) {
     // ---- validation: no HIP call before this block has passed ----
     if (n_layers < 0) return TF_ERR_INVALID_ARG;
     if (!valid_dtype(io_dtype) || !valid_dtype(dw_dtype)) return TF_ERR_DTYPE;
@@ -508,6 +407,108 @@ static int stage_backward_impl(tf_ctx* ctx, void* hip_stream,
     if (e != hipSuccess) return hip_fail(ctx, e);
     return TF_OK;
 }
+
+
+}  // namespace
+
+extern "C" {
+
+const char* tf_version(void) { return "0.1.0"; }
+
+const char* tf_strerror(int code) {
+    switch (code) {
+        case TF_OK: return "ok";
+        case TF_ERR_INVALID_ARG: return "invalid argument";
+        case TF_ERR_SHAPE: return "invalid shape or size";
+        case TF_ERR_DTYPE: return "unsupported dtype or dtype combination";
+        case TF_ERR_ALIGN: return "device pointer is not 16-byte aligned";
+        case TF_ERR_WORKSPACE: return "workspace allocation failed";
+        case TF_ERR_HIP: return "HIP runtime error (see tf_last_hip_error)";
+        case TF_ERR_NO_DEVICE: return "no usable gfx950 device";
+        case TF_ERR_ALIAS: return "an output buffer overlaps an input or another output";
+        default: return "unknown status code";
+    }
+}
+
+int tf_create(tf_ctx** out, int device_id) {
+    if (!out || device_id < 0) return TF_ERR_INVALID_ARG;
+    *out = nullptr;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device_id >= count) return TF_ERR_NO_DEVICE;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, device_id) != hipSuccess) return TF_ERR_NO_DEVICE;
+    if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return TF_ERR_NO_DEVICE;
+    if (hipSetDevice(device_id) != hipSuccess) return TF_ERR_NO_DEVICE;
+    tf_ctx* ctx = new (std::nothrow) tf_ctx;
+    if (!ctx) return TF_ERR_WORKSPACE;
+    ctx->device_id = device_id;
+    ctx->last_hip_error = 0;
+    ctx->profiling = false;
+    ctx->rc_state = nullptr;
+    ctx->rc_state_static = nullptr;
+    ctx->lowp_is_rounded_master = false;
+    ctx->ew_partials = nullptr;
+    if (hipMalloc(reinterpret_cast<void**>(&ctx->rc_state), tf::rc_state_bytes()) != hipSuccess) {
+        delete ctx;
+        return TF_ERR_WORKSPACE;
+    }
+    void* st = nullptr;
+    if (static_scratch_address(device_id, &st) != hipSuccess ||      // device_id is current here
+        hipMalloc(reinterpret_cast<void**>(&ctx->ew_partials), tf::ew_partials_bytes()) != hipSuccess ||
+        hipMemset(ctx->ew_partials, 0, tf::ew_partials_bytes()) != hipSuccess) {
+        if (ctx->ew_partials) (void)hipFree(ctx->ew_partials);
+        (void)hipFree(ctx->rc_state);
+        delete ctx;
+        return TF_ERR_WORKSPACE;
+    }
+    ctx->rc_state_static = static_cast<tf::RcState*>(st);
+    *out = ctx;
+    return TF_OK;
+}
+
+int tf_destroy(tf_ctx* ctx) {
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    for (tf_prof_rec& r : ctx->recs) { (void)hipEventDestroy(r.start); (void)hipEventDestroy(r.stop); }
+    for (hipEvent_t e : ctx->pool) (void)hipEventDestroy(e);
+    if (ctx->rc_state) (void)hipFree(ctx->rc_state);
+    if (ctx->ew_partials) (void)hipFree(ctx->ew_partials);
+    delete ctx;
+    return TF_OK;
+}
+
+int tf_assume_lowp_is_rounded_master(tf_ctx* ctx, int on) {
+    if (!ctx || (on != 0 && on != 1)) return TF_ERR_INVALID_ARG;
+    ctx->lowp_is_rounded_master = on != 0;
+    return TF_OK;
+}
+
+int tf_profile_enable(tf_ctx* ctx, int enable) {
+    if (!ctx || (enable != 0 && enable != 1)) return TF_ERR_INVALID_ARG;
+    ctx->profiling = enable != 0;
+    return TF_OK;
+}
+
+int tf_profile_collect(tf_ctx* ctx, int32_t capacity, int32_t* kinds, float* ms, int32_t* n_out) {
+    if (!ctx || !n_out || capacity < 0 || (capacity > 0 && (!kinds || !ms))) return TF_ERR_INVALID_ARG;
+    int32_t n = 0;
+    int rc = TF_OK;
+    for (tf_prof_rec& r : ctx->recs) {
+        if (n < capacity && rc == TF_OK) {
+            hipError_t e = hipEventSynchronize(r.stop);
+            float t = 0.f;
+            if (e == hipSuccess) e = hipEventElapsedTime(&t, r.start, r.stop);
+            if (e != hipSuccess) rc = hip_fail(ctx, e);
+            else { kinds[n] = r.kind; ms[n] = t; ++n; }
+        }
+        ctx->pool.push_back(r.start);
+        ctx->pool.push_back(r.stop);
+    }
+    ctx->recs.clear();
+    *n_out = n;
+    return rc;
+}
+
+int tf_last_hip_error(const tf_ctx* ctx) { return ctx ? ctx->last_hip_error : 0; }
 
 int tf_stage_backward_shared(tf_ctx* ctx, void* hip_stream,
                              int32_t n_layers, const tf_shape* shapes,
