@@ -73,8 +73,8 @@ typedef enum {
  * fails with TF_ERR_NO_DEVICE when there is no such device.  The context owns
  * its host-side bookkeeping (timing events) and two small device allocations, made
  * here: the 8.2 KB rank-search state of tf_reconcile_mask and 128 KB of partial
- * score sums for tf_masked_adamw / tf_stability_update (TF_ERR_WORKSPACE if
- * either fails).  No call allocates device memory afterwards.  Every later call on the
+ * sums for tf_masked_adamw / tf_stability_update / tf_autofreeze_norms
+ * (TF_ERR_WORKSPACE if either fails).  No call allocates device memory afterwards.  Every later call on the
  * context makes device_id current for the calling thread before it launches. */
 int tf_create(tf_ctx** out, int device_id);
 int tf_destroy(tf_ctx* ctx);
