@@ -164,10 +164,27 @@ __device__ __forceinline__ TilePos locate_tile(const GemmBatch& batch, int lt, i
 // ---------------------------------------------------------------------------------------------
 // Stage fill.  Load p of wave w fills KB number (4 p + w) of the 32 KB operand tile.
 //   kNT: that KB is tile rows R = 8 (4 p + w) + lane/8, physical chunk lane%8 of each row;
-//        logical chunk = physical ^ ((R ^ (R >> 3)) & 7).
+//        logical chunk = physical ^ nt_swizzle(R).
 //   kTN: that KB is contraction rows T = 2 (4 p + w) + lane/32, 16-byte slot lane%32 of
 //        each; logical 32-byte unit = physical unit ^ (4 ((T / 8) % 4) + T % 4).
 // ---------------------------------------------------------------------------------------------
+// kNT stage: which physical 16-byte chunk of its 128-byte row holds logical chunk c of tile row R:
+// c ^ nt_swizzle(R).  An operand read (ds_read_b128) takes 16 consecutive rows, lane l row l % 16,
+// logical chunk l / 16 (+ 4 for the second sub-step).  The LDS serves such a read 16 lanes at a
+// time, 8 consecutive lanes together with the 8 lanes 32 further on (counters: with a swizzle that
+// only kept 16 consecutive lanes apart, every read took twice its cycles): rows r .. r + 7 of
+// chunks q and q ^ 2 must fall into 16 different 16-byte bank groups, and a row's parity already
+// selects the half of the banks (row pitch 128 bytes).  Bits 1 and 2 of the row go to bits 0 and 2
+// of the swizzle, which the chunk pair does not touch; bit 3 of the row goes to bit 1, which
+// also keeps 16 consecutive lanes (one chunk, 16 rows) apart.
+__host__ __device__ __forceinline__ constexpr int nt_swizzle(int R) {
+#ifdef TF_NT_SWZ_OLD
+    return (R ^ (R >> 3)) & 7;
+#else
+    return ((R >> 1) & 1) | (((R >> 3) & 1) << 1) | (((R >> 2) & 1) << 2);
+#endif
+}
+
 struct Side {
     // One operand of a run.  Loads p = 0..3 of a stage fill go through (g, v[p]), loads 4..7
     // through (g2, v[p - 4]).
@@ -206,7 +223,7 @@ __device__ __forceinline__ Side make_side(const uint16_t* base, int64_t ld, int 
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int R = r + 8 * kWaves * p;
-            const int c = pc ^ ((R ^ (R >> 3)) & 7);           // the same for p and p + 4
+            const int c = pc ^ nt_swizzle(R);                  // the same for p and p + 4
             f.v[p] = uint32_t((int64_t(R) * ld + c * 8) * 2);
         }
         f.ks = 0;
@@ -351,12 +368,12 @@ __device__ __forceinline__ FragAddr make_frag_addr(int wm, int wn) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int ra = wm * 128 + i * 16 + lrow;
-            fa.a[i] = ra * 128 + ((lq ^ ((ra ^ (ra >> 3)) & 7)) << 4);
+            fa.a[i] = ra * 128 + ((lq ^ nt_swizzle(ra)) << 4);
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int rb = wn * 128 + j * 16 + lrow;
-            fa.b[j] = rb * 128 + ((lq ^ ((rb ^ (rb >> 3)) & 7)) << 4);
+            fa.b[j] = rb * 128 + ((lq ^ nt_swizzle(rb)) << 4);
         }
     }
     return fa;
