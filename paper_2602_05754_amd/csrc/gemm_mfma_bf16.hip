@@ -178,11 +178,7 @@ __device__ __forceinline__ TilePos locate_tile(const GemmBatch& batch, int lt, i
 // of the swizzle, which the chunk pair does not touch; bit 3 of the row goes to bit 1, which
 // also keeps 16 consecutive lanes (one chunk, 16 rows) apart.
 __host__ __device__ __forceinline__ constexpr int nt_swizzle(int R) {
-#ifdef TF_NT_SWZ_OLD
-    return (R ^ (R >> 3)) & 7;
-#else
     return ((R >> 1) & 1) | (((R >> 3) & 1) << 1) | (((R >> 2) & 1) << 2);
-#endif
 }
 
 struct Side {
